@@ -1,0 +1,193 @@
+/*
+ * qsac.h - C ABI of the MI355X (gfx950) QSAC decode step.
+ *
+ * One call to qsac_step() is one iteration of the loop of Algorithm 1
+ * (Section 4 of the LiteCache paper, arXiv 2511.14510) for one attention layer,
+ * for every (batch element, KV head) pair at once:
+ *
+ *   1. cache lookup: CosSim (Section 3.1) between each query head and its cached
+ *      query label q_c, aggregated per KV head by Eq. (2) (Section 4.2), compared
+ *      with the head's threshold tau; "at or above" reuses;
+ *   2. on a miss: exact qkscores (Eq. (1)) of the head's query group against all
+ *      N keys, S[n] = max over the group of q_g . k_n; the k best under (score
+ *      descending, index ascending); a diff of that set against the tokens held
+ *      by the head's cache slots; a fill of the missing rows only, from the K / V
+ *      fill sources (HBM or host-mapped pinned memory); q_c <- q_t;
+ *   3. softmax(q K_c^T / sqrt(d_k)) V_c over the k cached rows (Section 2.1).
+ *
+ * Every step runs in hand-written HIP kernels on the caller's streams.  All
+ * buffers are caller-owned; the library allocates no device memory, never
+ * synchronises inside qsac_step(), and keeps its own state (validity flags,
+ * the sorted index set of each head, scratch) in the caller's workspace.
+ *
+ * Conventions: "e" is a 16-bit float (IEEE binary16 or bfloat16, chosen at
+ * init).  P = batch * n_kv_heads pairs, pair p = b * n_kv_heads + h.
+ * G = n_q_heads / n_kv_heads; query head g of pair p is b * n_q_heads + h*G + g.
+ * D = head_dim = 128.  Tensors are dense, row-major, last index fastest.
+ * "device-accessible" means HBM or host memory mapped into the device
+ * (hipHostMalloc); every such pointer must be 16-byte aligned.
+ *
+ * Error behaviour: every function returns 0 (QSAC_OK) or a negative code; no
+ * exceptions, no aborts.  Arguments are validated on the host before anything
+ * is enqueued, so a failed call has no effect on the device.
+ */
+#ifndef QSAC_H
+#define QSAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { QSAC_F16 = 0, QSAC_BF16 = 1 };
+
+enum {
+  QSAC_OK = 0,
+  QSAC_EINVAL = -1,     /* a field has an unsupported value                     */
+  QSAC_ENULL = -2,      /* a required pointer is NULL                           */
+  QSAC_ERANGE = -3,     /* k, k_max, n_ctx or a head count is out of range      */
+  QSAC_EWORKSPACE = -4, /* workspace missing, misaligned or too small           */
+  QSAC_EHIP = -5,       /* a HIP runtime call failed (see qsac_last_hip_error)  */
+  QSAC_ESTATE = -6,     /* bad handle, or k changed without qsac_reset          */
+  QSAC_EALIGN = -7      /* a tensor pointer is not 16-byte aligned              */
+};
+
+enum {
+  QSAC_MAX_GROUP = 8,      /* largest supported G                                */
+  QSAC_MAX_KV_HEADS = 64,  /* largest supported n_kv_heads                       */
+  QSAC_HEAD_DIM = 128
+};
+
+/* qsac_config.flags */
+enum {
+  QSAC_FLAG_DRY_RUN = 1,     /* validate only: the ctx never touches a device (for hosts without a GPU) */
+  QSAC_FLAG_SERIAL = 2,      /* run the miss fill on stream_main even when stream_side is given           */
+  QSAC_FLAG_SCORE_VALU = 4,  /* score with packed dot-product ALU ops instead of the MFMA tile           */
+  QSAC_FLAG_PROFILE = 8      /* bracket every stage with timing events (single stream; see qsac_get_stage_ms) */
+};
+
+typedef struct qsac_ctx qsac_ctx;
+
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim must be 128; n_q_heads % n_kv_heads == 0 */
+  int64_t n_ctx;                /* N, fixed for the life of the ctx; 1 <= N <= 2^24                      */
+  int32_t k_max;                /* slot stride of the cache tensors; 1 <= k <= k_max <= N                */
+  int32_t dtype;                /* QSAC_F16 | QSAC_BF16: type of q, K, V, prev_q and the slots           */
+  const float *q_head_importance; /* HOST, [n_q_heads] weights s_j of Eq. (2), all > 0; NULL = all 1     */
+  void *stream_main;            /* hipStream_t (NULL = default stream); borrowed                          */
+  void *stream_side;            /* hipStream_t for the miss fill, or NULL to fill on stream_main; borrowed */
+  void *workspace;              /* DEVICE, 256-byte aligned, >= qsac_workspace_bytes(); caller-owned       */
+  size_t workspace_bytes;
+  int32_t flags;
+} qsac_config;
+
+/* Byte offsets of the library's arrays inside the workspace (for tests and tools that inspect them). */
+typedef struct {
+  size_t valid;      /* u32 [P]              1 once the head's cache has been filled                      */
+  size_t set_sorted; /* i32 [P][k_max]       the head's cached index set, ascending                       */
+  size_t keys;       /* u32 [P][n_pad]       order-preserving image of the fp32 scores of the last miss   */
+  size_t hist;       /* u32 [P][3][2048]     radix histograms of the last miss                            */
+  size_t bm_new;     /* u32 [P][words]       bitmap of the selected set                                   */
+  size_t bm_eq;      /* u32 [P][words]       bitmap of keys equal to the k-th key                         */
+  size_t bm_old;     /* u32 [P][words]       bitmap of the tokens cached before the step                  */
+  size_t miss_count; /* i32 [P]              rows filled by the last step (0 on reuse)                    */
+  size_t miss_slot;  /* i32 [P][k_max]       slots refilled, ascending                                    */
+  size_t miss_tok;   /* i32 [P][k_max]       tokens fetched, ascending; pairs with miss_slot              */
+  size_t part_ml;    /* f32 [P][G][splits][2]   running max (log2 domain) and sum of each attention split */
+  size_t part_acc;   /* f32 [P][G][splits][128] unnormalised partial outputs                              */
+  size_t stats;      /* u64 [8]              cumulative counters                                          */
+  size_t importance; /* f64 [n_q_heads]      Eq. (2) weights                                              */
+  size_t sel_r;      /* i32 [P]              keys equal to the k-th key that belong to the set (last miss)        */
+  size_t total;      /* bytes needed                                                                      */
+  int64_t n_pad;     /* N rounded up to the select chunk                                                  */
+  int32_t words;     /* 32-bit words per bitmap                                                           */
+  int32_t max_splits;/* attention splits provisioned per pair                                             */
+} qsac_ws_layout;
+
+/*
+ * Arguments of one step.  Everything is caller-owned and stays valid until
+ * stream_main has run past the step.
+ */
+typedef struct {
+  const void *q;        /* DEVICE e [B,Hq,D]        current queries q_t                                      */
+  const void *K_dev;    /* DEVICE e [B,Hkv,N,D]     full K in HBM, read by the scoring pass                  */
+  const void *K_src;    /* device-accessible e [B,Hkv,N,D]  fill source of K rows (may equal K_dev)          */
+  const void *V_src;    /* device-accessible e [B,Hkv,N,D]  fill source of V rows                            */
+  void *K_slots;        /* DEVICE e [B,Hkv,k_max,D] in/out  Replaceable Cache, K half (Section 3.3)          */
+  void *V_slots;        /* DEVICE e [B,Hkv,k_max,D] in/out  Replaceable Cache, V half                        */
+  int32_t *slot_idx;    /* DEVICE [B,Hkv,k_max]     in/out  token held by each slot                          */
+  void *prev_q;         /* DEVICE e [B,Hq,D]        in/out  query label q_c; rewritten only on a miss         */
+  const float *tau;     /* HOST [n_tau]             thresholds tau_i; n_tau is 1 (all heads) or n_kv_heads    */
+  int32_t n_tau;
+  int32_t k;            /* slots in use; constant between resets                                            */
+  float *out;           /* DEVICE f32 [B,Hq,D]      attention output                                         */
+  int32_t *topk_idx;    /* DEVICE [B,Hkv,k]         tokens in the head's cache after the step, ascending      */
+  uint8_t *hit_mask;    /* DEVICE [B,Hkv,k]         1 where topk_idx[j] was cached before the step           */
+  uint8_t *reuse_flags; /* DEVICE [B,Hkv]           1 where the gate reused the cached set                   */
+  float *sim;           /* DEVICE f32 [B,Hq] or NULL  per-query-head CosSim                                   */
+} qsac_step_args;
+
+/* Cumulative since init / reset, summed over pairs. */
+typedef struct {
+  uint64_t steps;        /* calls to qsac_step                          */
+  uint64_t reuse_heads;  /* pairs that took the reuse branch            */
+  uint64_t miss_heads;   /* pairs that took the miss branch             */
+  uint64_t slot_hits;    /* rows of a fresh top-k that were cached      */
+  uint64_t slot_misses;  /* rows filled from the fill sources           */
+  uint64_t reserved[3];
+} qsac_stats;
+
+/* Workspace size for a configuration (pure host function; 0 if the configuration is invalid). */
+size_t qsac_workspace_bytes(const qsac_config *cfg);
+
+/* Layout of the workspace (pure host function). */
+int qsac_workspace_layout(const qsac_config *cfg, qsac_ws_layout *out);
+
+/*
+ * Creates a context and marks every head's cache invalid, so the first step of every
+ * head is a miss that fills all k slots whatever tau is (Algorithm 1, line 1, assumes a
+ * cache filled at step 0; this is that step).  Enqueues a clear of the workspace
+ * bookkeeping on stream_main.  The ctx itself is host memory owned by the library.
+ */
+int qsac_init(const qsac_config *cfg, qsac_ctx **out);
+
+/* Marks every head's cache invalid again and zeroes the counters (enqueued on stream_main). */
+int qsac_reset(qsac_ctx *ctx);
+
+/*
+ * Enqueues one step (Algorithm 1, lines 3-18).  Results are valid once stream_main has run
+ * past it.  The slot contents, slot_idx and prev_q need no initialisation before the first
+ * step.  Inputs must be finite.
+ */
+int qsac_step(qsac_ctx *ctx, const qsac_step_args *args);
+
+/* Synchronises stream_main and copies the counters to host_out. */
+int qsac_get_stats(qsac_ctx *ctx, qsac_stats *host_out);
+
+/* Releases the ctx (host memory and the two events it owns).  Does not touch caller buffers. */
+int qsac_free(qsac_ctx *ctx);
+
+const char *qsac_strerror(int code);
+
+/* hipError_t of the last failing HIP call on this thread (0 if none). */
+int qsac_last_hip_error(void);
+
+/*
+ * Stage timing, for contexts created with QSAC_FLAG_PROFILE.  The stages of a step, in launch
+ * order, are: 0 gate, 1 score, 2 refine level 1, 3 refine level 2, 4 mark, 5 diff, 6 fill,
+ * 7 attention, 8 combine.  qsac_get_stage_ms() waits for the last profiled step and writes the
+ * summed duration of each stage in milliseconds to ms_sum[qsac_num_stages()] and the number of
+ * steps summed to *n_steps.  A duration is the time between the events recorded on stream_main
+ * before the stage's kernel and before the next one.  qsac_stage_name(i) is the kernel's name
+ * as a profiler trace shows it (without template arguments), NULL past the end.
+ */
+int qsac_num_stages(void);
+const char *qsac_stage_name(int i);
+int qsac_get_stage_ms(qsac_ctx *ctx, double *ms_sum, uint64_t *n_steps);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QSAC_H */

@@ -1,0 +1,472 @@
+// Host side of the QSAC C ABI (include/qsac.h): argument validation, workspace layout and the
+// launch sequence of one step.  No device memory is allocated here; everything lives in the
+// caller's workspace.
+#include "qsac.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "qsac_kernels.hip.h"
+
+using namespace qsac;
+
+namespace {
+
+constexpr uint32_t kMagic = 0x51534143u;  // "QSAC"
+constexpr int kStages = 9;
+const char* const kStageNames[kStages] = {"qsac_gate_kernel",      "qsac_score",       "qsac_refine_kernel<1>",
+                                          "qsac_refine_kernel<2>", "qsac_mark_kernel", "qsac_diff_kernel",
+                                          "qsac_fill_kernel",      "qsac_attn_kernel", "qsac_combine_kernel"};
+
+thread_local int g_last_hip = 0;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_config(const qsac_config* c) {
+  if (!c) return QSAC_ENULL;
+  if (c->head_dim != QSAC_HEAD_DIM) return QSAC_EINVAL;
+  if (c->dtype != QSAC_F16 && c->dtype != QSAC_BF16) return QSAC_EINVAL;
+  if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return QSAC_ERANGE;
+  if (c->n_kv_heads > QSAC_MAX_KV_HEADS) return QSAC_ERANGE;
+  if (c->n_q_heads % c->n_kv_heads != 0) return QSAC_EINVAL;
+  if (c->n_q_heads / c->n_kv_heads > QSAC_MAX_GROUP) return QSAC_ERANGE;
+  if (c->n_ctx < 1 || c->n_ctx > (int64_t(1) << 24)) return QSAC_ERANGE;
+  if (c->k_max < 1 || c->k_max > c->n_ctx) return QSAC_ERANGE;
+  if ((int64_t)c->batch * c->n_kv_heads > 65535) return QSAC_ERANGE;  // grid.y
+  if (c->flags & ~(QSAC_FLAG_DRY_RUN | QSAC_FLAG_SERIAL | QSAC_FLAG_SCORE_VALU | QSAC_FLAG_PROFILE)) return QSAC_EINVAL;
+  if (c->q_head_importance)
+    for (int i = 0; i < c->n_q_heads; ++i)
+      if (!(c->q_head_importance[i] > 0.f) || !std::isfinite(c->q_head_importance[i])) return QSAC_EINVAL;
+  return QSAC_OK;
+}
+
+// Attention split: rows of slots per workgroup for k slots in use.  Aims at >= 1024 workgroups
+// (four per compute unit) while keeping at least 64 rows, i.e. one 16-row tile per wave, each.
+int attn_rows(int P, int k) {
+  int64_t rows = ((int64_t)P * k + 1023) / 1024;
+  rows = (rows + 63) / 64 * 64;
+  if (rows < 64) rows = 64;
+  if (rows > 512) rows = 512;
+  return (int)rows;
+}
+
+void make_layout(const qsac_config* c, qsac_ws_layout* L) {
+  const size_t P = (size_t)c->batch * c->n_kv_heads;
+  const size_t G = (size_t)(c->n_q_heads / c->n_kv_heads);
+  const size_t n_pad = align_up((size_t)c->n_ctx, kSelChunk);
+  const size_t words = n_pad / 32;
+  const size_t splits = ((size_t)c->k_max + 63) / 64;  // rows per split is never below 64
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  L->valid = take(P * 4);
+  L->set_sorted = take(P * c->k_max * 4);
+  L->keys = take(P * n_pad * 4);
+  L->hist = take(P * 3 * kBins * 4);
+  L->bm_new = take(P * words * 4);
+  L->bm_eq = take(P * words * 4);
+  L->bm_old = take(P * words * 4);
+  L->miss_count = take(P * 4);
+  L->miss_slot = take(P * c->k_max * 4);
+  L->miss_tok = take(P * c->k_max * 4);
+  L->part_ml = take(P * G * splits * 2 * 4);
+  L->part_acc = take(P * G * splits * kD * 4);
+  L->stats = take(8 * 8);
+  L->importance = take((size_t)c->n_q_heads * 8);
+  L->sel_r = take(P * 4);
+  L->total = off;
+  L->n_pad = (int64_t)n_pad;
+  L->words = (int32_t)words;
+  L->max_splits = (int32_t)splits;
+}
+
+}  // namespace
+
+struct qsac_ctx {
+  uint32_t magic;
+  qsac_config cfg;
+  qsac_ws_layout L;
+  int P, G;
+  int k_bound;  // k of the steps since the last reset, 0 if none yet
+  uint64_t steps;
+  hipStream_t s_main, s_side;
+  hipEvent_t ev_sel, ev_fill;
+  bool dry, overlap, profile;
+  hipEvent_t prof[kStages + 1];
+  double stage_ms[kStages];
+  uint64_t stage_calls;
+  bool prof_pending;
+};
+
+namespace {
+
+#define HIP_TRY(expr)                 \
+  do {                                \
+    hipError_t e_ = (expr);           \
+    if (e_ != hipSuccess) {           \
+      g_last_hip = (int)e_;           \
+      return QSAC_EHIP;               \
+    }                                 \
+  } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int clear_state(qsac_ctx* c) {
+  char* ws = static_cast<char*>(c->cfg.workspace);
+  // bookkeeping that must start at zero: validity flags, counters (fill kernel, not a memset node)
+  qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.valid), (size_t)c->P);
+  qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.stats), (size_t)16);
+  qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.miss_count), (size_t)c->P);
+  HIP_TRY(hipGetLastError());
+  c->k_bound = 0;
+  c->steps = 0;
+  for (int i = 0; i < kStages; ++i) c->stage_ms[i] = 0.0;
+  c->stage_calls = 0;
+  c->prof_pending = false;
+  return QSAC_OK;
+}
+
+int drain_profile(qsac_ctx* c) {
+  if (!c->prof_pending) return QSAC_OK;
+  HIP_TRY(hipEventSynchronize(c->prof[kStages]));
+  for (int i = 0; i < kStages; ++i) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, c->prof[i], c->prof[i + 1]));
+    c->stage_ms[i] += ms;
+  }
+  c->stage_calls += 1;
+  c->prof_pending = false;
+  return QSAC_OK;
+}
+
+template <int DT, int G>
+void launch_score(const qsac_ctx* c, const qsac_step_args* a, dim3 grid, u32* keys, u32* hist) {
+  auto q = static_cast<const uint16_t*>(a->q);
+  auto K = static_cast<const uint16_t*>(a->K_dev);
+  if (c->cfg.flags & QSAC_FLAG_SCORE_VALU)
+    qsac_score_valu_kernel<DT, G><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, c->cfg.n_q_heads,
+                                                               c->cfg.n_kv_heads, c->cfg.n_ctx, c->L.n_pad);
+  else
+    qsac_score_mfma_kernel<DT, G><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, c->cfg.n_q_heads,
+                                                               c->cfg.n_kv_heads, c->cfg.n_ctx, c->L.n_pad);
+}
+
+template <int DT, int G>
+void launch_attn(const qsac_ctx* c, const qsac_step_args* a, dim3 grid, float* part_ml, float* part_acc, int rows,
+                 int which) {
+  qsac_attn_kernel<DT, G><<<grid, 256, 0, c->s_main>>>(
+      static_cast<const uint16_t*>(a->q), static_cast<const v4u*>(a->K_slots), static_cast<const v4u*>(a->V_slots),
+      a->reuse_flags, part_ml, part_acc, c->cfg.n_q_heads, c->cfg.n_kv_heads, a->k, c->cfg.k_max, rows,
+      c->L.max_splits, which);
+}
+
+// Dispatch on (dtype, G) to the instantiated kernels.
+#define QSAC_DISPATCH_G(FN, DT, ...)            \
+  switch (c->G) {                               \
+    case 1: FN<DT, 1>(__VA_ARGS__); break;      \
+    case 2: FN<DT, 2>(__VA_ARGS__); break;      \
+    case 3: FN<DT, 3>(__VA_ARGS__); break;      \
+    case 4: FN<DT, 4>(__VA_ARGS__); break;      \
+    case 5: FN<DT, 5>(__VA_ARGS__); break;      \
+    case 6: FN<DT, 6>(__VA_ARGS__); break;      \
+    case 7: FN<DT, 7>(__VA_ARGS__); break;      \
+    default: FN<DT, 8>(__VA_ARGS__); break;     \
+  }
+#define QSAC_DISPATCH(FN, ...)                                  \
+  do {                                                          \
+    if (c->cfg.dtype == QSAC_F16) {                             \
+      QSAC_DISPATCH_G(FN, 0, __VA_ARGS__)                       \
+    } else {                                                    \
+      QSAC_DISPATCH_G(FN, 1, __VA_ARGS__)                       \
+    }                                                           \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+size_t qsac_workspace_bytes(const qsac_config* cfg) {
+  if (check_config(cfg) != QSAC_OK) return 0;
+  qsac_ws_layout L;
+  make_layout(cfg, &L);
+  return L.total;
+}
+
+int qsac_workspace_layout(const qsac_config* cfg, qsac_ws_layout* out) {
+  if (!out) return QSAC_ENULL;
+  int rc = check_config(cfg);
+  if (rc != QSAC_OK) return rc;
+  make_layout(cfg, out);
+  return QSAC_OK;
+}
+
+int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
+  if (!out) return QSAC_ENULL;
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc != QSAC_OK) return rc;
+  qsac_ws_layout L;
+  make_layout(cfg, &L);
+  const bool dry = (cfg->flags & QSAC_FLAG_DRY_RUN) != 0;
+  if (!dry) {
+    if (!cfg->workspace) return QSAC_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(cfg->workspace) & 255u) return QSAC_EWORKSPACE;
+    if (cfg->workspace_bytes < L.total) return QSAC_EWORKSPACE;
+  }
+  qsac_ctx* c = new (std::nothrow) qsac_ctx();
+  if (!c) return QSAC_EINVAL;
+  c->magic = kMagic;
+  c->cfg = *cfg;
+  c->cfg.q_head_importance = nullptr;  // copied below; the caller's array is not kept
+  c->L = L;
+  c->P = cfg->batch * cfg->n_kv_heads;
+  c->G = cfg->n_q_heads / cfg->n_kv_heads;
+  c->dry = dry;
+  c->s_main = static_cast<hipStream_t>(cfg->stream_main);
+  c->s_side = static_cast<hipStream_t>(cfg->stream_side);
+  c->overlap = cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main && !(cfg->flags & QSAC_FLAG_SERIAL);
+  c->profile = (cfg->flags & QSAC_FLAG_PROFILE) != 0;
+  if (c->profile) c->overlap = false;  // stage times are taken on one stream
+  c->k_bound = 0;
+  c->steps = 0;
+  c->ev_sel = c->ev_fill = nullptr;
+  for (auto& e : c->prof) e = nullptr;
+  if (dry) {
+    *out = c;
+    return QSAC_OK;
+  }
+  auto fail = [&](int code) {
+    qsac_free(c);
+    return code;
+  };
+  if (hipEventCreateWithFlags(&c->ev_sel, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_fill, hipEventDisableTiming) != hipSuccess) {
+    g_last_hip = (int)hipGetLastError();
+    return fail(QSAC_EHIP);
+  }
+  if (c->profile)
+    for (auto& e : c->prof)
+      if (hipEventCreate(&e) != hipSuccess) {
+        g_last_hip = (int)hipGetLastError();
+        return fail(QSAC_EHIP);
+      }
+  // Eq. (2) weights, widened to fp64 on the host; a synchronous copy, so the staging buffer can go.
+  {
+    double* w = static_cast<double*>(std::malloc(sizeof(double) * (size_t)cfg->n_q_heads));
+    if (!w) return fail(QSAC_EINVAL);
+    for (int i = 0; i < cfg->n_q_heads; ++i) w[i] = cfg->q_head_importance ? (double)cfg->q_head_importance[i] : 1.0;
+    hipError_t e = hipMemcpy(static_cast<char*>(cfg->workspace) + L.importance, w,
+                             sizeof(double) * (size_t)cfg->n_q_heads, hipMemcpyHostToDevice);
+    std::free(w);
+    if (e != hipSuccess) {
+      g_last_hip = (int)e;
+      return fail(QSAC_EHIP);
+    }
+  }
+  rc = clear_state(c);
+  if (rc != QSAC_OK) return fail(rc);
+  *out = c;
+  return QSAC_OK;
+}
+
+int qsac_reset(qsac_ctx* c) {
+  if (!c || c->magic != kMagic) return QSAC_ESTATE;
+  c->k_bound = 0;
+  c->steps = 0;
+  if (c->dry) return QSAC_OK;
+  return clear_state(c);
+}
+
+int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
+  if (!c || c->magic != kMagic) return QSAC_ESTATE;
+  if (!a) return QSAC_ENULL;
+  if (!a->q || !a->K_dev || !a->K_src || !a->V_src || !a->K_slots || !a->V_slots || !a->slot_idx || !a->prev_q ||
+      !a->tau || !a->out || !a->topk_idx || !a->hit_mask || !a->reuse_flags)
+    return QSAC_ENULL;
+  if (a->n_tau != 1 && a->n_tau != c->cfg.n_kv_heads) return QSAC_EINVAL;
+  for (int i = 0; i < a->n_tau; ++i)
+    if (std::isnan(a->tau[i])) return QSAC_EINVAL;
+  if (a->k < 1 || a->k > c->cfg.k_max) return QSAC_ERANGE;
+  if (c->k_bound != 0 && a->k != c->k_bound) return QSAC_ESTATE;
+  const void* al[] = {a->q, a->K_dev, a->K_src, a->V_src, a->K_slots, a->V_slots, a->slot_idx, a->prev_q, a->out, a->topk_idx};
+  for (const void* ptr : al)
+    if (!aligned16(ptr)) return QSAC_EALIGN;
+  c->k_bound = a->k;
+  c->steps += 1;
+  if (c->dry) return QSAC_OK;
+
+  const qsac_ws_layout& L = c->L;
+  char* ws = static_cast<char*>(c->cfg.workspace);
+  u32* valid = reinterpret_cast<u32*>(ws + L.valid);
+  int* set_sorted = reinterpret_cast<int*>(ws + L.set_sorted);
+  u32* keys = reinterpret_cast<u32*>(ws + L.keys);
+  u32* hist = reinterpret_cast<u32*>(ws + L.hist);
+  u32* bm_new = reinterpret_cast<u32*>(ws + L.bm_new);
+  u32* bm_eq = reinterpret_cast<u32*>(ws + L.bm_eq);
+  u32* bm_old = reinterpret_cast<u32*>(ws + L.bm_old);
+  int* miss_count = reinterpret_cast<int*>(ws + L.miss_count);
+  int* miss_slot = reinterpret_cast<int*>(ws + L.miss_slot);
+  int* miss_tok = reinterpret_cast<int*>(ws + L.miss_tok);
+  float* part_ml = reinterpret_cast<float*>(ws + L.part_ml);
+  float* part_acc = reinterpret_cast<float*>(ws + L.part_acc);
+  u64* stats = reinterpret_cast<u64*>(ws + L.stats);
+  const double* importance = reinterpret_cast<const double*>(ws + L.importance);
+  int* sel_r = reinterpret_cast<int*>(ws + L.sel_r);
+
+  const int P = c->P, G = c->G, k = a->k, k_max = c->cfg.k_max;
+  const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
+  const int64_t N = c->cfg.n_ctx;
+  hipStream_t sm = c->s_main;
+
+  if (c->profile) {
+    int rc = drain_profile(c);
+    if (rc != QSAC_OK) return rc;
+  }
+  auto mark = [&](int i) {
+    if (c->profile) (void)hipEventRecord(c->prof[i], sm);
+  };
+
+  TauArg tau;
+  for (int h = 0; h < Hkv; ++h) tau.v[h] = a->tau[a->n_tau == 1 ? 0 : h];
+
+  // 1. gate (+ label update on a miss)
+  mark(0);
+  if (c->cfg.dtype == QSAC_F16)
+    qsac_gate_kernel<0><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
+                                           importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
+                                           a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max);
+  else
+    qsac_gate_kernel<1><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
+                                           importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
+                                           a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max);
+  // 2. scores of the missing pairs (+ level-0 histogram)
+  mark(1);
+  {
+    dim3 grid((unsigned)((N + kScoreRows - 1) / kScoreRows), (unsigned)P);
+    QSAC_DISPATCH(launch_score, c, a, grid, keys, hist);
+  }
+  // 3. radix select of the k-th key, bitmaps
+  dim3 sel_grid((unsigned)(L.n_pad / kSelChunk), (unsigned)P);
+  mark(2);
+  qsac_refine_kernel<1><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
+  mark(3);
+  qsac_refine_kernel<2><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
+  mark(4);
+  qsac_mark_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, bm_new, bm_eq, bm_old, sel_r, N, L.n_pad,
+                                            L.words, k);
+  // 4. diff against the cache slots
+  mark(5);
+  qsac_diff_kernel<<<P, kDiffThreads, 0, sm>>>(a->reuse_flags, valid, bm_new, bm_eq, bm_old, sel_r, a->slot_idx,
+                                              set_sorted, a->topk_idx, a->hit_mask, miss_count, miss_slot, miss_tok,
+                                              stats, L.words, k, k_max);
+  // 5. fill the missing rows; 6. attention
+  const int rows = attn_rows(P, k);
+  const int n_splits = (k + rows - 1) / rows;
+  dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
+  dim3 attn_grid((unsigned)n_splits, (unsigned)P);
+  auto fill_on = [&](hipStream_t s) {
+    qsac_fill_kernel<<<fill_grid, 256, 0, s>>>(miss_count, miss_slot, miss_tok, static_cast<const v4u*>(a->K_src),
+                                               static_cast<const v4u*>(a->V_src), static_cast<v4u*>(a->K_slots),
+                                               static_cast<v4u*>(a->V_slots), N, k_max);
+  };
+  auto attend = [&](int which) {
+    QSAC_DISPATCH(launch_attn, c, a, attn_grid, part_ml, part_acc, rows, which);
+  };
+  auto combine = [&](int which) {
+    qsac_combine_kernel<<<P * G, 128, 0, sm>>>(part_ml, part_acc, a->reuse_flags, a->out, Hq, Hkv, G, n_splits,
+                                               L.max_splits, which);
+  };
+  if (c->overlap) {
+    // the fill runs on the side stream while the pairs that reused their cache are attended to
+    HIP_TRY(hipEventRecord(c->ev_sel, sm));
+    HIP_TRY(hipStreamWaitEvent(c->s_side, c->ev_sel, 0));
+    fill_on(c->s_side);
+    HIP_TRY(hipEventRecord(c->ev_fill, c->s_side));
+    attend(1);
+    HIP_TRY(hipStreamWaitEvent(sm, c->ev_fill, 0));
+    attend(2);
+    combine(0);
+  } else {
+    mark(6);
+    fill_on(sm);
+    mark(7);
+    attend(0);
+    mark(8);
+    combine(0);
+    mark(9);
+    c->prof_pending = c->profile;
+  }
+  HIP_TRY(hipGetLastError());
+  return QSAC_OK;
+}
+
+int qsac_get_stats(qsac_ctx* c, qsac_stats* out) {
+  if (!c || c->magic != kMagic) return QSAC_ESTATE;
+  if (!out) return QSAC_ENULL;
+  std::memset(out, 0, sizeof *out);
+  out->steps = c->steps;
+  if (c->dry) return QSAC_OK;
+  unsigned long long dev[8];
+  HIP_TRY(hipStreamSynchronize(c->s_main));
+  HIP_TRY(hipMemcpy(dev, static_cast<char*>(c->cfg.workspace) + c->L.stats, sizeof dev, hipMemcpyDeviceToHost));
+  out->reuse_heads = dev[1];
+  out->miss_heads = dev[2];
+  out->slot_hits = dev[3];
+  out->slot_misses = dev[4];
+  return QSAC_OK;
+}
+
+int qsac_get_stage_ms(qsac_ctx* c, double* ms_sum, uint64_t* n_steps) {
+  if (!c || c->magic != kMagic) return QSAC_ESTATE;
+  if (!ms_sum || !n_steps) return QSAC_ENULL;
+  if (!c->profile) return QSAC_ESTATE;
+  if (!c->dry) {
+    int rc = drain_profile(c);
+    if (rc != QSAC_OK) return rc;
+  }
+  for (int i = 0; i < kStages; ++i) ms_sum[i] = c->stage_ms[i];
+  *n_steps = c->stage_calls;
+  return QSAC_OK;
+}
+
+int qsac_free(qsac_ctx* c) {
+  if (!c || c->magic != kMagic) return QSAC_ESTATE;
+  if (!c->dry) {
+    if (c->ev_sel) (void)hipEventDestroy(c->ev_sel);
+    if (c->ev_fill) (void)hipEventDestroy(c->ev_fill);
+    for (auto& e : c->prof)
+      if (e) (void)hipEventDestroy(e);
+  }
+  c->magic = 0;
+  delete c;
+  return QSAC_OK;
+}
+
+const char* qsac_strerror(int code) {
+  switch (code) {
+    case QSAC_OK: return "ok";
+    case QSAC_EINVAL: return "invalid value in an argument";
+    case QSAC_ENULL: return "required pointer is NULL";
+    case QSAC_ERANGE: return "size or count out of range";
+    case QSAC_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case QSAC_EHIP: return "HIP runtime call failed";
+    case QSAC_ESTATE: return "bad handle or call out of order";
+    case QSAC_EALIGN: return "pointer is not 16-byte aligned";
+    default: return "unknown error";
+  }
+}
+
+int qsac_last_hip_error(void) { return g_last_hip; }
+
+int qsac_num_stages(void) { return kStages; }
+
+const char* qsac_stage_name(int i) { return (i >= 0 && i < kStages) ? kStageNames[i] : nullptr; }
+
+}  // extern "C"

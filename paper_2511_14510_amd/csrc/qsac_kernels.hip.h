@@ -1,0 +1,815 @@
+// Device code of the QSAC decode step for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// Stages, in launch order (one iteration of Algorithm 1 of the LiteCache paper for every
+// (batch, KV head) pair p at once):
+//   gate     cache lookup: CosSim (Section 3.1) per query head in fp64, Eq. (2) per KV head,
+//            label update q_c <- q_t on a miss (the paper fuses the two as well, Section 6.2)
+//   score    Eq. (1) for the head's query group against all N keys, S[n] = max_g q_g.k_n,
+//            stored as order-preserving 32-bit keys, with the first radix histogram fused in
+//   refine1, refine2, mark
+//            radix select of the k-th largest key (11 + 11 + 10 bits), then bitmaps of the
+//            keys above it and equal to it
+//   diff     ties by lowest index, ascending index list, hit mask against the cached tokens,
+//            (slot, token) miss list, slot table update
+//   fill     copies the missing K / V rows from the fill sources into the slots
+//   attn     softmax(q K_c^T / sqrt(d)) V_c over the slots (Section 2.1), split over slots
+//   combine  merges the splits
+//
+// Pairs whose gate reused the cache leave every miss-path kernel at once.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qsac {
+
+typedef uint32_t u32;
+typedef unsigned long long u64;
+
+constexpr int kD = 128;            // head_dim
+constexpr int kRowU4 = 16;         // 16-byte chunks per 256-byte row
+constexpr int kBins = 2048;        // bins per radix level (level 2 uses the first 1024)
+constexpr int kScoreRows = 1024;   // keys per workgroup of the scoring kernel
+constexpr int kSelChunk = 8192;    // keys per workgroup of the select passes
+constexpr int kFillRows = 64;      // miss-list entries per workgroup of the fill kernel
+constexpr int kDiffThreads = 1024;
+
+typedef __attribute__((ext_vector_type(2))) _Float16 half2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf2_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 half8_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf8_t;
+typedef __attribute__((ext_vector_type(4))) float f4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t v4u;  // one 16-byte load
+
+struct TauArg {
+  float v[64];  // per KV head
+};
+
+// ---------------------------------------------------------------- small helpers
+
+__device__ __forceinline__ u32 fbits(float f) { return __builtin_bit_cast(u32, f); }
+__device__ __forceinline__ float bitsf(u32 u) { return __builtin_bit_cast(float, u); }
+
+// Order-preserving image of a finite fp32: a > b  <=>  key(a) > key(b); -0 ranks as +0.
+__device__ __forceinline__ u32 ordered_key(float f) {
+  u32 u = fbits(f);
+  if ((u << 1) == 0) u = 0;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+template <int DT>
+__device__ __forceinline__ float lo16(u32 w) {
+  if (DT == 0) return (float)__builtin_bit_cast(half2_t, w)[0];
+  return bitsf(w << 16);
+}
+template <int DT>
+__device__ __forceinline__ float hi16(u32 w) {
+  if (DT == 0) return (float)__builtin_bit_cast(half2_t, w)[1];
+  return bitsf(w & 0xffff0000u);
+}
+
+template <int DT>
+__device__ __forceinline__ float dot2(u32 a, u32 b, float acc) {
+  if (DT == 0) return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), acc, false);
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2_t, a), __builtin_bit_cast(bf2_t, b), acc, false);
+}
+template <int DT>
+__device__ __forceinline__ float dot8(v4u a, v4u b) {
+  float s = dot2<DT>(a.x, b.x, 0.f);
+  s = dot2<DT>(a.y, b.y, s);
+  s = dot2<DT>(a.z, b.z, s);
+  return dot2<DT>(a.w, b.w, s);
+}
+
+template <int DT>
+__device__ __forceinline__ f4_t mfma16(v4u a, v4u b, f4_t c) {
+  if (DT == 0) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8_t, a), __builtin_bit_cast(bf8_t, b), c, 0, 0, 0);
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the same total.
+// All 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return bitsf((u32)__builtin_amdgcn_update_dpp(0, (int)fbits(v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);  // row_half_mirror
+  v += dpp_move<0x140>(v);  // row_mirror
+  return v;
+}
+
+// Exclusive prefix sum of one int per thread over a workgroup of NW wavefronts; *total gets the sum.
+// Contains barriers: every thread of the workgroup must call it.
+template <int NW>
+__device__ __forceinline__ int block_exclusive_scan(int v, int* s_wave /*[NW+1]*/, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    int t = __shfl_up(inc, d);
+    if (lane >= d) inc += t;
+  }
+  __syncthreads();  // s_wave may still be read from a previous call
+  if (lane == 63) s_wave[wave] = inc;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    int t = s_wave[w];
+    if (w < wave) base += t;
+    tot += t;
+  }
+  *total = tot;
+  return base + inc - v;
+}
+
+// Among bins [0, nbins) of `hist`, finds the bin b with  count(bins > b) < need <= count(bins >= b).
+// Returns b; *above = count(bins > b).  256 threads; contains barriers.
+__device__ __forceinline__ int find_bin(const u32* __restrict__ hist, int nbins, int need, int* above,
+                                        int* s_wave, int* s_res) {
+  const int per = nbins / 256;  // 8 or 4
+  // thread t owns bins [hi - per + 1, hi] counted from the top: t = 0 owns the highest bins
+  const int hi = nbins - 1 - (int)threadIdx.x * per;
+  int c[8];
+  int local = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    c[i] = (i < per) ? (int)hist[hi - i] : 0;
+    local += c[i];
+  }
+  if (threadIdx.x == 0) {
+    s_res[0] = 0;
+    s_res[1] = 0;
+  }
+  int tot;
+  int before = block_exclusive_scan<4>(local, s_wave, &tot);  // keys in bins above this thread's
+  if (before < need && need <= before + local) {
+    int run = before;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (i < per) {
+        if (run < need && need <= run + c[i]) {
+          s_res[0] = hi - i;
+          s_res[1] = run;
+        }
+        run += c[i];
+      }
+    }
+  }
+  __syncthreads();
+  int b = s_res[0];
+  *above = s_res[1];
+  __syncthreads();
+  return b;
+}
+
+// ---------------------------------------------------------------- gate
+
+// One workgroup (256 threads) per pair.  Wave w takes query heads w, w+4, ...; each lane two
+// elements.  The three dot products, the norms and Eq. (2) are taken in fp64: products of two
+// 16-bit floats are exact there, so the reuse decision matches an fp64 reference unless the
+// aggregate sits within ~1e-15 of tau.
+template <int DT>
+__global__ __launch_bounds__(256) void qsac_gate_kernel(
+    const uint16_t* __restrict__ q, uint16_t* __restrict__ prev_q, const double* __restrict__ importance,
+    TauArg tau, const u32* __restrict__ valid, const int* __restrict__ set_sorted, int* __restrict__ topk_idx,
+    uint8_t* __restrict__ hit_mask, uint8_t* __restrict__ reuse_flags, float* __restrict__ sim_out,
+    int* __restrict__ miss_count, u32* __restrict__ hist, u64* __restrict__ stats, int Hq, int Hkv, int G,
+    int k, int k_max) {
+  const int p = blockIdx.x;
+  const int b = p / Hkv, h = p % Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __shared__ double s_sim[8];
+  __shared__ int s_reuse;
+  const size_t head0 = (size_t)b * Hq + (size_t)h * G;
+  const u32* q32 = reinterpret_cast<const u32*>(q) + head0 * (kD / 2);
+  u32* pq32 = reinterpret_cast<u32*>(prev_q) + head0 * (kD / 2);
+
+  for (int g = wave; g < G; g += 4) {
+    u32 a = q32[g * 64 + lane], c = pq32[g * 64 + lane];
+    double a0 = (double)lo16<DT>(a), a1 = (double)hi16<DT>(a);
+    double c0 = (double)lo16<DT>(c), c1 = (double)hi16<DT>(c);
+    double ab = a0 * c0 + a1 * c1, aa = a0 * a0 + a1 * a1, cc = c0 * c0 + c1 * c1;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+      ab += __shfl_xor(ab, d);
+      aa += __shfl_xor(aa, d);
+      cc += __shfl_xor(cc, d);
+    }
+    if (lane == 0) {
+      double s = (aa == 0.0 || cc == 0.0) ? -1.0 : ab / (sqrt(aa) * sqrt(cc));
+      s_sim[g] = s;
+      if (sim_out) sim_out[head0 + g] = (float)s;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double num = 0.0, den = 0.0;
+    bool nonpos = false;
+    for (int g = 0; g < G; ++g) {
+      double w = importance[h * G + g];
+      double s = s_sim[g];
+      if (s <= 0.0) nonpos = true;
+      num += w;
+      den += w / s;
+    }
+    double agg = nonpos ? -1.0 : num / den;
+    int reuse = (valid[p] != 0) && (agg >= (double)tau.v[h]);
+    s_reuse = reuse;
+    reuse_flags[p] = (uint8_t)reuse;
+    atomicAdd(&stats[reuse ? 1 : 2], 1ull);
+  }
+  __syncthreads();
+  if (s_reuse) {
+    // cache hit: report the cached set as it stands
+    const int* src = set_sorted + (size_t)p * k_max;
+    for (int j = threadIdx.x; j < k; j += 256) {
+      topk_idx[(size_t)p * k + j] = src[j];
+      hit_mask[(size_t)p * k + j] = 1;
+    }
+    if (threadIdx.x == 0) miss_count[p] = 0;
+  } else {
+    // cache miss: relabel now (the rows follow in the fill), and clear this pair's histograms
+    for (int i = threadIdx.x; i < G * 64; i += 256) pq32[i] = q32[i];
+    u32* hp = hist + (size_t)p * 3 * kBins;
+    for (int i = threadIdx.x; i < 3 * kBins; i += 256) hp[i] = 0;
+  }
+}
+
+// ---------------------------------------------------------------- score
+
+// After the key tile of a workgroup sits in LDS: write it out and add it to the level-0 histogram.
+__device__ __forceinline__ void score_epilogue(const u32* s_keys, u32* s_hist, u32* __restrict__ keys_p,
+                                               u32* __restrict__ hist_p, int64_t row0, int64_t N) {
+  __syncthreads();
+  const int t4 = threadIdx.x * 4;
+  v4u kk = *reinterpret_cast<const v4u*>(s_keys + t4);
+  *reinterpret_cast<v4u*>(keys_p + row0 + t4) = kk;
+  const int64_t n = row0 + t4;
+  if (n + 0 < N) atomicAdd(&s_hist[kk.x >> 21], 1u);
+  if (n + 1 < N) atomicAdd(&s_hist[kk.y >> 21], 1u);
+  if (n + 2 < N) atomicAdd(&s_hist[kk.z >> 21], 1u);
+  if (n + 3 < N) atomicAdd(&s_hist[kk.w >> 21], 1u);
+  __syncthreads();
+  for (int bin = threadIdx.x; bin < kBins; bin += 256) {
+    u32 c = s_hist[bin];
+    if (c) atomicAdd(&hist_p[bin], c);
+  }
+}
+
+// MFMA form.  Per wave and iteration a 16 x 128 tile of K meets the (zero-padded to 16) query
+// group in four v_mfma_f32_16x16x32: the query group is the A operand (row = query), the keys
+// are the B operand (column = key).  Lane l reads 64 contiguous bytes of key row l%16 (quarter
+// l/16 of the row); MFMA j contracts the j-th 16-byte piece of every quarter, and the query
+// fragments are cut the same way, so the products pair up correctly whatever order the
+// hardware sums them in.  acc[i] of lane l is the score of query 4*(l/16)+i against key l%16.
+template <int DT, int G>
+__global__ __launch_bounds__(256) void qsac_score_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint8_t* __restrict__ reuse_flags,
+    u32* __restrict__ keys, u32* __restrict__ hist, int Hq, int Hkv, int64_t N, int64_t n_pad) {
+  const int p = blockIdx.y;
+  if (reuse_flags[p]) return;
+  __shared__ u32 s_hist[kBins];
+  __shared__ __attribute__((aligned(16))) u32 s_keys[kScoreRows];
+  for (int i = threadIdx.x; i < kBins; i += 256) s_hist[i] = 0;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m = lane & 15, quarter = lane >> 4;
+  const int b = p / Hkv, h = p % Hkv;
+  const v4u* qg = reinterpret_cast<const v4u*>(q + ((size_t)b * Hq + (size_t)h * G) * kD);
+  v4u qa[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) qa[j] = (m < G) ? qg[m * kRowU4 + quarter * 4 + j] : v4u{0, 0, 0, 0};
+
+  const int64_t row0 = (int64_t)blockIdx.x * kScoreRows;
+  const v4u* Kp = reinterpret_cast<const v4u*>(K + (size_t)p * (size_t)N * kD);
+  const int wrow = wave * (kScoreRows / 4);
+
+  for (int it = 0; it < kScoreRows / 4 / 16; it += 4) {
+    v4u kb[4][4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      int64_t n = row0 + wrow + (it + u) * 16 + m;
+      n = n < N ? n : N - 1;
+      const v4u* src = Kp + n * kRowU4 + quarter * 4;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) kb[u][j] = __builtin_nontemporal_load(src + j);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc = mfma16<DT>(qa[j], kb[u][j], acc);
+      // lanes 0-15 hold queries 0-3, lanes 16-31 queries 4-7 (rows >= G are zero padding)
+      float s = acc[0];
+#pragma unroll
+      for (int i = 1; i < 4; ++i) {
+        const int gq = quarter * 4 + i;  // query this register belongs to
+        if (gq < G) s = fmaxf(s, acc[i]);
+      }
+      if (G > 4) {
+        float t = __shfl_down(s, 16);  // lane 16+m -> lane m
+        s = fmaxf(s, t);
+      }
+      const int r = wrow + (it + u) * 16 + m;
+      if (quarter == 0) s_keys[r] = (row0 + r < N) ? ordered_key(s) : 0u;
+    }
+  }
+  score_epilogue(s_keys, s_hist, keys + (size_t)p * n_pad, hist + (size_t)p * 3 * kBins, row0, N);
+}
+
+// Vector-ALU form.  A 16-lane DPP row takes one key row (16 bytes per lane), four rows per
+// wave-wide load; each lane forms G partial dot products with v_dot2 and the row sums them
+// through DPP.  Group r of the wave handles rows 4r..4r+3 of each 16-row tile.
+template <int DT, int G>
+__global__ __launch_bounds__(256) void qsac_score_valu_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint8_t* __restrict__ reuse_flags,
+    u32* __restrict__ keys, u32* __restrict__ hist, int Hq, int Hkv, int64_t N, int64_t n_pad) {
+  const int p = blockIdx.y;
+  if (reuse_flags[p]) return;
+  __shared__ u32 s_hist[kBins];
+  __shared__ __attribute__((aligned(16))) u32 s_keys[kScoreRows];
+  for (int i = threadIdx.x; i < kBins; i += 256) s_hist[i] = 0;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 15, r = lane >> 4;
+  const int b = p / Hkv, h = p % Hkv;
+  const v4u* qg = reinterpret_cast<const v4u*>(q + ((size_t)b * Hq + (size_t)h * G) * kD);
+  v4u qf[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) qf[g] = qg[g * kRowU4 + c];
+
+  const int64_t row0 = (int64_t)blockIdx.x * kScoreRows;
+  const v4u* Kp = reinterpret_cast<const v4u*>(K + (size_t)p * (size_t)N * kD);
+  const int wrow = wave * (kScoreRows / 4);
+
+  for (int it = 0; it < kScoreRows / 4 / 16; ++it) {
+    v4u kv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      int64_t n = row0 + wrow + it * 16 + r * 4 + u;
+      n = n < N ? n : N - 1;
+      kv[u] = __builtin_nontemporal_load(Kp + n * kRowU4 + c);
+    }
+    u32 out[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float best = row16_sum(dot8<DT>(qf[0], kv[u]));
+#pragma unroll
+      for (int g = 1; g < G; ++g) best = fmaxf(best, row16_sum(dot8<DT>(qf[g], kv[u])));
+      const int rr = wrow + it * 16 + r * 4 + u;
+      out[u] = (row0 + rr < N) ? ordered_key(best) : 0u;
+    }
+    if (c == 0) *reinterpret_cast<v4u*>(s_keys + wrow + it * 16 + r * 4) = v4u{out[0], out[1], out[2], out[3]};
+  }
+  score_epilogue(s_keys, s_hist, keys + (size_t)p * n_pad, hist + (size_t)p * 3 * kBins, row0, N);
+}
+
+// ---------------------------------------------------------------- radix select
+
+// LEVEL 1: histogram bits 20..10 of the keys whose bits 31..21 equal the level-0 threshold bin.
+// LEVEL 2: histogram bits 9..0 of the keys whose bits 31..10 equal the two-level prefix.
+// Every workgroup re-derives the prefix from the finished histograms of the levels above
+// (2048 counters, read from L2) instead of waiting for a separate one-workgroup kernel.
+template <int LEVEL>
+__global__ __launch_bounds__(256) void qsac_refine_kernel(const uint8_t* __restrict__ reuse_flags,
+                                                          const u32* __restrict__ keys, u32* __restrict__ hist,
+                                                          int64_t N, int64_t n_pad, int k) {
+  const int p = blockIdx.y;
+  if (reuse_flags[p]) return;
+  __shared__ u32 s_hist[kBins];
+  __shared__ int s_wave[5];
+  __shared__ int s_res[2];
+  u32* hp = hist + (size_t)p * 3 * kBins;
+  for (int i = threadIdx.x; i < kBins; i += 256) s_hist[i] = 0;
+  int above;
+  int need = k;
+  u32 prefix = (u32)find_bin(hp, kBins, need, &above, s_wave, s_res);
+  need -= above;
+  int shift = 21;
+  if (LEVEL == 2) {
+    u32 b1 = (u32)find_bin(hp + kBins, kBins, need, &above, s_wave, s_res);
+    prefix = (prefix << 11) | b1;
+    shift = 10;
+  }
+  const u32 mask = (LEVEL == 1) ? 0x7ffu : 0x3ffu;
+  const int sub = (LEVEL == 1) ? 10 : 0;
+  const int64_t base = (int64_t)blockIdx.x * kSelChunk;
+  const v4u* kp = reinterpret_cast<const v4u*>(keys + (size_t)p * n_pad + base);
+#pragma unroll
+  for (int i = 0; i < kSelChunk / 4 / 256; ++i) {
+    const int v = i * 256 + threadIdx.x;
+    v4u kk = kp[v];
+    const int64_t n = base + (int64_t)v * 4;
+    if (n + 0 < N && (kk.x >> shift) == prefix) atomicAdd(&s_hist[(kk.x >> sub) & mask], 1u);
+    if (n + 1 < N && (kk.y >> shift) == prefix) atomicAdd(&s_hist[(kk.y >> sub) & mask], 1u);
+    if (n + 2 < N && (kk.z >> shift) == prefix) atomicAdd(&s_hist[(kk.z >> sub) & mask], 1u);
+    if (n + 3 < N && (kk.w >> shift) == prefix) atomicAdd(&s_hist[(kk.w >> sub) & mask], 1u);
+  }
+  __syncthreads();
+  u32* out = hp + LEVEL * kBins;
+  for (int bin = threadIdx.x; bin < kBins; bin += 256) {
+    u32 c = s_hist[bin];
+    if (c) atomicAdd(&out[bin], c);
+  }
+}
+
+// With the k-th largest key T known exactly: bitmap of keys > T, bitmap of keys == T (64 keys
+// per wave-wide ballot), and a cleared bitmap for the cached tokens.
+__global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restrict__ reuse_flags,
+                                                        const u32* __restrict__ keys, const u32* __restrict__ hist,
+                                                        u32* __restrict__ bm_new, u32* __restrict__ bm_eq,
+                                                        u32* __restrict__ bm_old, int* __restrict__ sel_r,
+                                                        int64_t N, int64_t n_pad, int words, int k) {
+  const int p = blockIdx.y;
+  if (reuse_flags[p]) return;
+  __shared__ int s_wave[5];
+  __shared__ int s_res[2];
+  const u32* hp = hist + (size_t)p * 3 * kBins;
+  int above, need = k;
+  u32 b0 = (u32)find_bin(hp, kBins, need, &above, s_wave, s_res);
+  need -= above;
+  u32 b1 = (u32)find_bin(hp + kBins, kBins, need, &above, s_wave, s_res);
+  need -= above;
+  u32 b2 = (u32)find_bin(hp + 2 * kBins, 1024, need, &above, s_wave, s_res);
+  need -= above;  // number of keys equal to T that belong to the set (>= 1)
+  const u32 T = (b0 << 21) | (b1 << 10) | b2;
+  if (blockIdx.x == 0 && threadIdx.x == 0) sel_r[p] = need;
+
+  const int lane = threadIdx.x & 63;
+  const int64_t base = (int64_t)blockIdx.x * kSelChunk;
+  const u32* kp = keys + (size_t)p * n_pad;
+  u32* gt = bm_new + (size_t)p * words;
+  u32* eq = bm_eq + (size_t)p * words;
+  u32* old = bm_old + (size_t)p * words;
+#pragma unroll 4
+  for (int i = 0; i < kSelChunk / 256; ++i) {
+    const int64_t n = base + (int64_t)i * 256 + threadIdx.x;
+    const u32 key = kp[n];
+    const bool in = n < N;
+    const u64 mg = __ballot(in && key > T);
+    const u64 me = __ballot(in && key == T);
+    const int64_t w = n >> 5;  // lane 0 -> low word, lane 32 -> high word of this wave's 64 keys
+    if (lane == 0) {
+      gt[w] = (u32)mg;
+      eq[w] = (u32)me;
+      old[w] = 0;
+    } else if (lane == 32) {
+      gt[w] = (u32)(mg >> 32);
+      eq[w] = (u32)(me >> 32);
+      old[w] = 0;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- diff
+
+// One workgroup (1024 threads) per missing pair; thread t owns a contiguous run of bitmap words.
+//  A. ties: of the keys equal to T, the r with the lowest indices join the set;
+//  B. bitmap of the tokens cached before the step (from slot_idx);
+//  C. ascending index list, hit mask, ascending list of tokens to fetch;
+//  D. ascending list of slots whose token left the set;
+//  E. i-th such slot takes the i-th token to fetch.
+__global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
+    const uint8_t* __restrict__ reuse_flags, u32* __restrict__ valid, u32* __restrict__ bm_new,
+    const u32* __restrict__ bm_eq, u32* __restrict__ bm_old, const int* __restrict__ sel_r,
+    int* __restrict__ slot_idx, int* __restrict__ set_sorted, int* __restrict__ topk_idx,
+    uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count, int* __restrict__ miss_slot,
+    int* __restrict__ miss_tok, u64* __restrict__ stats, int words, int k, int k_max) {
+  const int p = blockIdx.x;
+  if (reuse_flags[p]) return;
+  __shared__ int s_wave[17];
+  const int tid = threadIdx.x;
+  u32* nw = bm_new + (size_t)p * words;
+  const u32* eq = bm_eq + (size_t)p * words;
+  u32* old = bm_old + (size_t)p * words;
+  int* sl = slot_idx + (size_t)p * k_max;
+  const bool was_valid = valid[p] != 0;
+  const int r = sel_r[p];
+  const int wpt = (words + kDiffThreads - 1) / kDiffThreads;
+  const int w0 = min(tid * wpt, words), w1 = min(w0 + wpt, words);
+  int total;
+
+  // A
+  int ceq = 0;
+  for (int w = w0; w < w1; ++w) ceq += __popc(eq[w]);
+  int rank = block_exclusive_scan<16>(ceq, s_wave, &total);
+  for (int w = w0; w < w1; ++w) {
+    u32 e = eq[w];
+    const int c = __popc(e);
+    if (rank + c > r) {  // keep only the lowest (r - rank) bits of e
+      int keep = r - rank;
+      u32 kept = 0;
+      while (keep > 0 && e) {
+        u32 low = e & (0u - e);
+        kept |= low;
+        e ^= low;
+        --keep;
+      }
+      e = kept;
+    }
+    rank += c;
+    if (e) nw[w] |= e;
+  }
+  // B
+  if (was_valid)
+    for (int j = tid; j < k; j += kDiffThreads) {
+      const int tok = sl[j];
+      atomicOr(&old[tok >> 5], 1u << (tok & 31));
+    }
+  __syncthreads();
+  // C
+  int cn = 0, cm = 0;
+  for (int w = w0; w < w1; ++w) {
+    const u32 a = nw[w], o = old[w];
+    cn += __popc(a);
+    cm += __popc(a & ~o);
+  }
+  int jn = block_exclusive_scan<16>(cn, s_wave, &total);
+  int jm = block_exclusive_scan<16>(cm, s_wave, &total);
+  int* tk = topk_idx + (size_t)p * k;
+  uint8_t* hm = hit_mask + (size_t)p * k;
+  int* ss = set_sorted + (size_t)p * k_max;
+  int* mt = miss_tok + (size_t)p * k_max;
+  int* ms = miss_slot + (size_t)p * k_max;
+  for (int w = w0; w < w1; ++w) {
+    u32 a = nw[w];
+    const u32 o = old[w];
+    while (a) {
+      const int bit = __ffs(a) - 1;
+      a &= a - 1;
+      const int tok = w * 32 + bit;
+      const bool hit = (o >> bit) & 1u;
+      if (jn < k) {  // the set has exactly k members; the guard only protects the buffers
+        tk[jn] = tok;
+        ss[jn] = tok;
+        hm[jn] = (uint8_t)hit;
+      }
+      ++jn;
+      if (!hit) {
+        if (jm < k) mt[jm] = tok;
+        ++jm;
+      }
+    }
+  }
+  // D
+  const int spt = (k + kDiffThreads - 1) / kDiffThreads;
+  const int j0 = min(tid * spt, k), j1 = min(j0 + spt, k);
+  int ce = 0;
+  for (int j = j0; j < j1; ++j) {
+    bool ev = true;
+    if (was_valid) {
+      const int tok = sl[j];
+      ev = !((nw[tok >> 5] >> (tok & 31)) & 1u);
+    }
+    ce += ev;
+  }
+  int je = block_exclusive_scan<16>(ce, s_wave, &total);
+  const int m = total;
+  for (int j = j0; j < j1; ++j) {
+    bool ev = true;
+    if (was_valid) {
+      const int tok = sl[j];
+      ev = !((nw[tok >> 5] >> (tok & 31)) & 1u);
+    }
+    if (ev) ms[je++] = j;
+  }
+  __syncthreads();
+  // E
+  for (int i = tid; i < m; i += kDiffThreads) sl[ms[i]] = mt[i];
+  if (tid == 0) {
+    miss_count[p] = m;
+    valid[p] = 1;
+    atomicAdd(&stats[3], (u64)(k - m));
+    atomicAdd(&stats[4], (u64)m);
+  }
+}
+
+// ---------------------------------------------------------------- fill
+
+// Copies the rows named by a pair's miss list into its slots.  A 16-lane group moves one
+// 256-byte row with one 16-byte load per lane; each group has four K and four V loads in
+// flight before the first store, which is what keeps enough reads outstanding when the
+// source is host memory behind PCIe.
+__global__ __launch_bounds__(256) void qsac_fill_kernel(const int* __restrict__ miss_count,
+                                                        const int* __restrict__ miss_slot,
+                                                        const int* __restrict__ miss_tok,
+                                                        const v4u* __restrict__ K_src, const v4u* __restrict__ V_src,
+                                                        v4u* __restrict__ K_slots, v4u* __restrict__ V_slots,
+                                                        int64_t N, int k_max) {
+  const int p = blockIdx.y;
+  const int m = miss_count[p];
+  const int e0 = blockIdx.x * kFillRows;
+  if (e0 >= m) return;
+  const int c = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int* ms = miss_slot + (size_t)p * k_max;
+  const int* mt = miss_tok + (size_t)p * k_max;
+  const v4u* Ks = K_src + (size_t)p * (size_t)N * kRowU4;
+  const v4u* Vs = V_src + (size_t)p * (size_t)N * kRowU4;
+  v4u* Kd = K_slots + (size_t)p * k_max * kRowU4;
+  v4u* Vd = V_slots + (size_t)p * k_max * kRowU4;
+  int slot[4];
+  v4u kr[4], vr[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int e = e0 + u * 16 + grp;
+    slot[u] = -1;
+    if (e < m) {
+      slot[u] = ms[e];
+      const size_t tok = (size_t)mt[e];
+      kr[u] = Ks[tok * kRowU4 + c];
+      vr[u] = Vs[tok * kRowU4 + c];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (slot[u] >= 0) {
+      Kd[(size_t)slot[u] * kRowU4 + c] = kr[u];
+      Vd[(size_t)slot[u] * kRowU4 + c] = vr[u];
+    }
+}
+
+// ---------------------------------------------------------------- attention
+
+// which: 0 = every pair, 1 = pairs that reused, 2 = pairs that missed.
+__device__ __forceinline__ bool pair_selected(int which, const uint8_t* reuse_flags, int p) {
+  return which == 0 || (which == 1) == (reuse_flags[p] != 0);
+}
+
+// Workgroup (split, pair): slots [split*rows, split*rows + rows) of the pair, all G query heads.
+// A 16-lane DPP row takes one slot per load (16 bytes of the K row and of the V row per lane);
+// its lanes form the G dot products with v_dot2, sum them over the row, and every lane keeps
+// its own online-softmax state (running max, sum, 8 output channels per head) for the slots of
+// its row group.  Tiles of 16 slots per wave share one rescale.  Row groups, then waves, are
+// merged at the end; the split's (max, sum, unnormalised output) goes to the workspace.
+template <int DT, int G>
+__global__ __launch_bounds__(256) void qsac_attn_kernel(
+    const uint16_t* __restrict__ q, const v4u* __restrict__ K_slots, const v4u* __restrict__ V_slots,
+    const uint8_t* __restrict__ reuse_flags, float* __restrict__ part_ml, float* __restrict__ part_acc, int Hq,
+    int Hkv, int k, int k_max, int rows, int max_splits, int which) {
+  const int p = blockIdx.y, split = blockIdx.x;
+  if (!pair_selected(which, reuse_flags, p)) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 15, r = lane >> 4;
+  const int b = p / Hkv, h = p % Hkv;
+  const v4u* qg = reinterpret_cast<const v4u*>(q + ((size_t)b * Hq + (size_t)h * G) * kD);
+  v4u qf[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) qf[g] = qg[g * kRowU4 + c];
+  const v4u* Kp = K_slots + (size_t)p * k_max * kRowU4;
+  const v4u* Vp = V_slots + (size_t)p * k_max * kRowU4;
+
+  const float kScale = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
+  const float kNegInf = -__builtin_inff();
+  float mx[G], sum[G], acc[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    mx[g] = kNegInf;
+    sum[g] = 0.f;
+#pragma unroll
+    for (int d = 0; d < 8; ++d) acc[g][d] = 0.f;
+  }
+
+  const int s_begin = split * rows;
+  const int s_end = min(s_begin + rows, k);
+  // wave w takes tiles w, w+4, ... of 16 slots; row group r takes slots 4r..4r+3 of the tile
+  for (int t0 = s_begin + wave * 16; t0 < s_end; t0 += 64) {
+    v4u kv[4], vv[4];
+    bool ok[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      int j = t0 + r * 4 + u;
+      ok[u] = j < s_end;
+      j = ok[u] ? j : s_end - 1;
+      kv[u] = Kp[(size_t)j * kRowU4 + c];
+      vv[u] = Vp[(size_t)j * kRowU4 + c];
+    }
+    float vf[4][8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      vf[u][0] = lo16<DT>(vv[u].x); vf[u][1] = hi16<DT>(vv[u].x);
+      vf[u][2] = lo16<DT>(vv[u].y); vf[u][3] = hi16<DT>(vv[u].y);
+      vf[u][4] = lo16<DT>(vv[u].z); vf[u][5] = hi16<DT>(vv[u].z);
+      vf[u][6] = lo16<DT>(vv[u].w); vf[u][7] = hi16<DT>(vv[u].w);
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float s[4];
+      float tmax = kNegInf;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        s[u] = row16_sum(dot8<DT>(qf[g], kv[u])) * kScale;
+        s[u] = ok[u] ? s[u] : kNegInf;
+        tmax = fmaxf(tmax, s[u]);
+      }
+      const float mnew = fmaxf(mx[g], tmax);
+      if (mnew != kNegInf) {  // at least one real slot so far
+        const float alpha = (mx[g] == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mx[g] - mnew);
+        float pw[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) pw[u] = ok[u] ? __builtin_amdgcn_exp2f(s[u] - mnew) : 0.f;
+        sum[g] = sum[g] * alpha + ((pw[0] + pw[1]) + (pw[2] + pw[3]));
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+          float a = acc[g][d] * alpha;
+          a = fmaf(pw[0], vf[0][d], a);
+          a = fmaf(pw[1], vf[1][d], a);
+          a = fmaf(pw[2], vf[2][d], a);
+          a = fmaf(pw[3], vf[3][d], a);
+          acc[g][d] = a;
+        }
+        mx[g] = mnew;
+      }
+    }
+  }
+
+  // merge the four row groups of the wave (lanes c, c+16, c+32, c+48)
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int sh = 16; sh <= 32; sh <<= 1) {
+      const float om = __shfl_xor(mx[g], sh);
+      const float os = __shfl_xor(sum[g], sh);
+      const float mnew = fmaxf(mx[g], om);
+      const float wa = (mx[g] == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mx[g] - mnew);
+      const float wb = (om == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(om - mnew);
+      sum[g] = sum[g] * wa + os * wb;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) {
+        const float oa = __shfl_xor(acc[g][d], sh);
+        acc[g][d] = acc[g][d] * wa + oa * wb;
+      }
+      mx[g] = mnew;
+    }
+  }
+  // merge the four waves through LDS
+  __shared__ float s_ml[4][G][2];
+  __shared__ float s_acc[4][G][kD];
+  if (r == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      if (c == 0) {
+        s_ml[wave][g][0] = mx[g];
+        s_ml[wave][g][1] = sum[g];
+      }
+#pragma unroll
+      for (int d = 0; d < 8; ++d) s_acc[wave][g][c * 8 + d] = acc[g][d];
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < G * kD; i += 256) {
+    const int g = i >> 7, d = i & 127;
+    float M = kNegInf;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, s_ml[w][g][0]);
+    float L = 0.f, A = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = s_ml[w][g][0];
+      const float wt = (mw == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+      L += s_ml[w][g][1] * wt;
+      A += s_acc[w][g][d] * wt;
+    }
+    const size_t slot = ((size_t)p * G + g) * max_splits + split;
+    part_acc[slot * kD + d] = A;
+    if (d == 0) {
+      part_ml[slot * 2 + 0] = M;
+      part_ml[slot * 2 + 1] = L;
+    }
+  }
+}
+
+// One workgroup of 128 threads per query head: merges the splits and normalises.
+__global__ __launch_bounds__(128) void qsac_combine_kernel(const float* __restrict__ part_ml,
+                                                           const float* __restrict__ part_acc,
+                                                           const uint8_t* __restrict__ reuse_flags,
+                                                           float* __restrict__ out, int Hq, int Hkv, int G,
+                                                           int n_splits, int max_splits, int which) {
+  const int pg = blockIdx.x;  // p * G + g
+  const int p = pg / G, g = pg % G;
+  if (!pair_selected(which, reuse_flags, p)) return;
+  const int d = threadIdx.x;
+  const float kNegInf = -__builtin_inff();
+  const float* ml = part_ml + (size_t)pg * max_splits * 2;
+  const float* pa = part_acc + (size_t)pg * max_splits * kD;
+  float M = kNegInf;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml[s * 2]);
+  float L = 0.f, A = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float ms = ml[s * 2];
+    const float wt = (ms == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+    L += ml[s * 2 + 1] * wt;
+    A += pa[(size_t)s * kD + d] * wt;
+  }
+  const int b = p / Hkv, h = p % Hkv;
+  out[((size_t)b * Hq + (size_t)h * G + g) * kD + d] = A / L;
+}
+
+// Clears `n` 32-bit words (used instead of a memset node so that the step can be captured in a graph).
+__global__ __launch_bounds__(256) void qsac_zero_kernel(u32* __restrict__ ptr, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) ptr[i] = 0;
+}
+
+}  // namespace qsac

@@ -1,0 +1,149 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes the workspace, and turns bad arguments into error codes before anything
+is enqueued (dry-run contexts never touch a device)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2511_14510_amd import binding as Q
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(Q.LIB_PATH):
+        from paper_2511_14510_amd import build
+        build.build()
+    return Q.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    text = open(os.path.join(ROOT, "include", "qsac.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(qsac_[a-z_]+)\s*\(", text))
+    assert declared == set(Q.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_sizes_match_the_header(lib):
+    # a mismatch between the ctypes mirror and the C structs would corrupt every call
+    src = r'''
+    #include "qsac.h"
+    #include <stdio.h>
+    int main(void){ printf("%zu %zu %zu %zu\n", sizeof(qsac_config), sizeof(qsac_ws_layout), sizeof(qsac_step_args), sizeof(qsac_stats)); return 0; }
+    '''
+    import subprocess, tempfile
+    with tempfile.TemporaryDirectory() as d:
+        open(os.path.join(d, "s.c"), "w").write(src)
+        subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), "-o", os.path.join(d, "s"), os.path.join(d, "s.c")])
+        sizes = [int(x) for x in subprocess.check_output([os.path.join(d, "s")]).split()]
+    assert sizes == [C.sizeof(Q.qsac_config), C.sizeof(Q.qsac_ws_layout), C.sizeof(Q.qsac_step_args), C.sizeof(Q.qsac_stats)]
+
+
+def test_workspace_size_and_layout(lib):
+    cfg = Q.make_config(8, 32, 8, 32768, 2048, Q.QSAC_BF16)
+    n = Q.qsac_workspace_bytes(cfg)
+    L = Q.qsac_workspace_layout(cfg)
+    assert n == L.total and n > 64 * 32768 * 4
+    assert L.n_pad == 32768 and L.words == 1024 and L.max_splits == 32
+    offs = [getattr(L, f) for f, _ in Q.qsac_ws_layout._fields_[:15]]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    cfg = Q.make_config(1, 8, 2, 5000, 100, Q.QSAC_F16)
+    assert Q.qsac_workspace_layout(cfg).n_pad == 8192
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(D=64), Q.QSAC_EINVAL),
+    (dict(dtype=7), Q.QSAC_EINVAL),
+    (dict(Hq=9), Q.QSAC_EINVAL),          # 9 % 2 != 0
+    (dict(Hq=18), Q.QSAC_ERANGE),         # G = 9 > 8
+    (dict(B=0), Q.QSAC_ERANGE),
+    (dict(N=0), Q.QSAC_ERANGE),
+    (dict(N=(1 << 24) + 1), Q.QSAC_ERANGE),
+    (dict(k_max=0), Q.QSAC_ERANGE),
+    (dict(k_max=4097), Q.QSAC_ERANGE),    # k_max > N
+    (dict(Hkv=65, Hq=65), Q.QSAC_ERANGE),
+    (dict(flags=1 << 20), Q.QSAC_EINVAL),
+    (dict(importance=[1, 1, 1, 0, 1, 1, 1, 1]), Q.QSAC_EINVAL),
+])
+def test_bad_configs_are_rejected(lib, kw, code):
+    a = dict(B=1, Hq=8, Hkv=2, N=4096, k_max=256, dtype=Q.QSAC_F16, flags=Q.QSAC_FLAG_DRY_RUN, importance=None, D=128)
+    a.update(kw)
+    cfg = Q.make_config(a["B"], a["Hq"], a["Hkv"], a["N"], a["k_max"], a["dtype"], a["flags"], a["importance"])
+    cfg.head_dim = a["D"]
+    assert Q.qsac_workspace_bytes(cfg) == 0
+    ctx = C.c_void_p()
+    assert lib.qsac_init(C.byref(cfg), C.byref(ctx)) == code
+    assert not ctx.value
+
+
+def test_workspace_checks_without_dry_run(lib):
+    cfg = Q.make_config(1, 8, 2, 4096, 256, Q.QSAC_F16)
+    ctx = C.c_void_p()
+    assert lib.qsac_init(C.byref(cfg), C.byref(ctx)) == Q.QSAC_EWORKSPACE     # no workspace
+    cfg.workspace, cfg.workspace_bytes = 0x1000100, 16                          # too small
+    assert lib.qsac_init(C.byref(cfg), C.byref(ctx)) == Q.QSAC_EWORKSPACE
+    cfg.workspace, cfg.workspace_bytes = 0x1000010, 1 << 30                     # misaligned
+    assert lib.qsac_init(C.byref(cfg), C.byref(ctx)) == Q.QSAC_EWORKSPACE
+    assert lib.qsac_init(None, C.byref(ctx)) == Q.QSAC_ENULL
+    assert lib.qsac_init(C.byref(cfg), None) == Q.QSAC_ENULL
+
+
+def _args(**over):
+    a = Q.qsac_step_args()
+    for f, _ in Q.qsac_step_args._fields_:
+        if f not in ("tau", "n_tau", "k"):
+            setattr(a, f, 0x10000)
+    tau = (C.c_float * 2)(0.9, 0.8)
+    a._keep = tau
+    a.tau, a.n_tau, a.k = C.cast(tau, C.POINTER(C.c_float)), 1, 256
+    for key, v in over.items():
+        setattr(a, key, v)
+    return a
+
+
+def test_step_validation_on_a_dry_run_context(lib):
+    cfg = Q.make_config(1, 8, 2, 4096, 256, Q.QSAC_F16, Q.QSAC_FLAG_DRY_RUN)
+    ctx = Q.qsac_init(cfg)
+    step = lambda a: lib.qsac_step(ctx, C.byref(a))
+    assert lib.qsac_step(ctx, None) == Q.QSAC_ENULL
+    assert lib.qsac_step(None, C.byref(_args())) == Q.QSAC_ESTATE
+    for f in ("q", "K_dev", "K_src", "V_src", "K_slots", "V_slots", "slot_idx", "prev_q", "out", "topk_idx",
+              "hit_mask", "reuse_flags"):
+        assert step(_args(**{f: None})) == Q.QSAC_ENULL, f
+    assert step(_args(tau=C.POINTER(C.c_float)())) == Q.QSAC_ENULL
+    assert step(_args(sim=None)) == Q.QSAC_OK                      # sim is optional
+    Q.qsac_reset(ctx)
+    assert step(_args(n_tau=3)) == Q.QSAC_EINVAL                   # neither 1 nor n_kv_heads
+    assert step(_args(n_tau=2)) == Q.QSAC_OK
+    nan = (C.c_float * 1)(float("nan"))
+    assert step(_args(tau=C.cast(nan, C.POINTER(C.c_float)))) == Q.QSAC_EINVAL
+    assert step(_args(k=0)) == Q.QSAC_ERANGE
+    assert step(_args(k=257)) == Q.QSAC_ERANGE
+    assert step(_args(q=0x10008)) == Q.QSAC_EALIGN
+    assert step(_args(k=128)) == Q.QSAC_ESTATE                     # k changed without a reset
+    Q.qsac_reset(ctx)
+    assert step(_args(k=128)) == Q.QSAC_OK
+    st = Q.qsac_get_stats(ctx)
+    assert st["steps"] == 1 and st["reuse_heads"] == 0
+    Q.qsac_free(ctx)
+    assert lib.qsac_free(None) == Q.QSAC_ESTATE
+    assert lib.qsac_reset(None) == Q.QSAC_ESTATE
+
+
+def test_strerror_and_stage_names(lib):
+    for code in range(0, -8, -1):
+        assert Q.qsac_strerror(code) != "unknown error"
+    assert Q.qsac_strerror(-99) == "unknown error"
+    n = lib.qsac_num_stages()
+    assert n == 9 and lib.qsac_stage_name(n) is None
+    assert lib.qsac_stage_name(0) == b"qsac_gate_kernel" and lib.qsac_stage_name(7) == b"qsac_attn_kernel"
+
+
+def test_binding_has_no_cpu_fallback():
+    src = open(os.path.join(ROOT, "paper_2511_14510_amd", "binding.py")).read()
+    assert "oracle" not in src.replace("no other implementation", "")

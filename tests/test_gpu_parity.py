@@ -1,0 +1,203 @@
+"""GPU parity: every case drives the HIP kernels through the C ABI and checks each step against
+the oracle (tests/gpu_harness.py states the bars)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2511_14510_amd import binding as Q
+from paper_2511_14510_amd import workload as W
+
+
+@pytest.fixture(scope="module")
+def H():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    Q.load()
+    import gpu_harness
+    return gpu_harness
+
+
+def run_chain(H, B, Hq, Hkv, N, k, k_max, dtype, steps, tau=0.9, rho=0.95, seed=3, flags=0, importance=None,
+              host_k=False, host_v=False, q_norm=1.0, side_stream=True, expect_both=True):
+    print(f"case B={B} Hq={Hq} Hkv={Hkv} N={N} k={k} k_max={k_max} {dtype} steps={steps} tau={tau} rho={rho} "
+          f"seed={seed} flags={flags} host=({host_k},{host_v}) q_norm={q_norm}", flush=True)
+    sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, N, k_max, dtype, seed, host_k, host_v, flags, importance, side_stream)
+    par = H.Parity(sess, dtype, Kb, Ksb, Vsb, importance)
+    chain = W.QueryChain(B, Hq, 128, rho, seed, q_norm=q_norm)
+    for t in range(steps):
+        par.step(chain.next(), tau, k, label=f"step {t}")
+    st = sess.stats()
+    assert st["steps"] == steps
+    assert st["reuse_heads"] == par.n_reuse and st["miss_heads"] == par.n_miss
+    assert st["slot_misses"] == par.filled and st["slot_hits"] == par.n_miss * k - par.filled
+    if expect_both:
+        assert par.n_reuse > 0 and par.n_miss > B * Hkv
+    sess.close()
+    return par
+
+
+def test_tiny_config_full_run(H):
+    """BASELINE config 1 in full: 1 x 8q/2kv, N=4096, k=256, fp16, tau=0.9, 64 steps."""
+    w = W.CONFIGS["tiny"]
+    par = run_chain(H, w.B, w.Hq, w.Hkv, w.N, w.k, w.k, w.dtype, w.steps, w.tau, w.rho, w.seed)
+    assert 0.3 < par.n_reuse / (par.n_reuse + par.n_miss) < 0.95
+
+
+@pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_SCORE_VALU, Q.QSAC_FLAG_SERIAL, Q.QSAC_FLAG_PROFILE])
+def test_ragged_shapes_gqa5_bf16(H, flags):
+    """N, k and k_max off every tile size (1024-key score tiles, 8192-key select chunks, 64-row
+    fill and attention tiles), G = 5 as in the Qwen2.5-14B shape."""
+    run_chain(H, B=2, Hq=10, Hkv=2, N=9001, k=300, k_max=333, dtype="bf16", steps=16, flags=flags)
+
+
+@pytest.mark.parametrize("G,dtype", [(1, "f16"), (2, "bf16"), (3, "f16"), (4, "bf16"), (6, "bf16"), (7, "f16"), (8, "bf16")])
+@pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_SCORE_VALU])
+def test_group_sizes(H, G, dtype, flags):
+    run_chain(H, B=1, Hq=2 * G, Hkv=2, N=2500, k=130, k_max=130, dtype=dtype, steps=10, flags=flags, seed=10 + G)
+
+
+@pytest.mark.parametrize("N,k", [(1, 1), (3, 3), (17, 1), (64, 64), (100, 99), (1024, 1), (1025, 1025)])
+def test_degenerate_sizes(H, N, k):
+    run_chain(H, B=1, Hq=4, Hkv=1, N=N, k=k, k_max=k, dtype="bf16", steps=6, tau=0.97, expect_both=False)
+
+
+def test_tau_above_one_refreshes_every_step(H):
+    par = run_chain(H, B=1, Hq=8, Hkv=2, N=3000, k=200, k_max=200, dtype="bf16", steps=8, tau=2.0, expect_both=False)
+    assert par.n_reuse == 0
+
+
+def test_tau_minus_one_keeps_the_first_set(H):
+    par = run_chain(H, B=1, Hq=8, Hkv=2, N=3000, k=200, k_max=200, dtype="f16", steps=8, tau=-1.0, rho=0.2,
+                    expect_both=False)
+    assert par.n_miss == 2 and par.n_reuse == 14
+
+
+def test_k_equals_N_matches_dense_attention(H):
+    """With k = N the sparse step is dense attention; after the first step nothing is ever fetched."""
+    par = run_chain(H, B=1, Hq=8, Hkv=2, N=777, k=777, k_max=777, dtype="bf16", steps=8, tau=0.93)
+    assert par.filled == 2 * 777
+
+
+def test_peaked_softmax_and_outlier_values(H):
+    """||q|| = 2 sqrt(D): logits spread over hundreds of units, the online rescaling is exercised."""
+    run_chain(H, B=1, Hq=8, Hkv=2, N=4000, k=512, k_max=512, dtype="bf16", steps=10, q_norm=2 * np.sqrt(128.0))
+
+
+def test_fill_from_pinned_host_memory(H):
+    run_chain(H, B=2, Hq=8, Hkv=2, N=6000, k=384, k_max=400, dtype="bf16", steps=12, host_k=True, host_v=True)
+    run_chain(H, B=1, Hq=8, Hkv=2, N=6000, k=384, k_max=384, dtype="f16", steps=8, host_v=True, side_stream=False)
+
+
+def test_per_head_tau_and_importance(H):
+    imp = [0.2, 1.0, 3.0, 0.7, 1.0, 1.0, 0.1, 2.5]
+    par = run_chain(H, B=2, Hq=8, Hkv=2, N=2000, k=100, k_max=100, dtype="bf16", steps=16, tau=[0.95, 0.8],
+                    importance=imp)
+    assert par.n_reuse > 0
+
+
+def test_many_pairs_long_rows(H):
+    """More pairs than compute-unit waves in flight, and an N that spans several select chunks."""
+    run_chain(H, B=8, Hq=16, Hkv=4, N=20000, k=640, k_max=640, dtype="bf16", steps=6)
+
+
+def exact_tie_case(H, flags):
+    """K entries in {-1, 0, 1} and queries with a few small-integer entries: every score is a small
+    integer, exact in fp32 and fp64 alike, with hundreds of exact ties across the k-th score - the
+    index sets must match exactly under the lowest-index tie-break."""
+    B, Hq, Hkv, N, k = 1, 4, 2, 5000, 257
+    rng = np.random.default_rng(99)
+    K = torch.from_numpy(rng.integers(-1, 2, (B, Hkv, N, 128)).astype(np.float32)).to(torch.bfloat16)
+    V = torch.from_numpy(rng.standard_normal((B, Hkv, N, 128)).astype(np.float32)).to(torch.bfloat16)
+    sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, N, k, "bf16", flags=flags, K=K, V=V)
+    par = H.Parity(sess, "bf16", Kb, Ksb, Vsb)
+    for t in range(6):
+        q = np.zeros((B, Hq, 128))
+        for hq in range(Hq):
+            pos = rng.choice(128, 6, replace=False)
+            q[0, hq, pos] = rng.integers(-2, 3, 6)
+            q[0, hq, pos[0]] = 1
+        r = par.step(q, 2.0, k, label=f"ties step {t}")
+        for p in range(2):
+            kth = r.kth_score[p]
+            assert (r.scores[p] == kth).sum() > 20          # the k-th score really is tied
+    assert par.n_band == 0
+    sess.close()
+
+
+@pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_SCORE_VALU])
+def test_exact_ties_take_the_lowest_index(H, flags):
+    exact_tie_case(H, flags)
+
+
+def test_all_keys_equal_selects_the_first_k(H):
+    B, Hq, Hkv, N, k = 1, 4, 1, 9000, 100
+    row = torch.randn(128, generator=torch.Generator().manual_seed(1))
+    K = row.expand(B, Hkv, N, 128).contiguous().to(torch.float16)
+    V = torch.randn((B, Hkv, N, 128), generator=torch.Generator().manual_seed(2)).to(torch.float16)
+    sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, N, k, "f16", K=K, V=V)
+    par = H.Parity(sess, "f16", Kb, Ksb, Vsb)
+    chain = W.QueryChain(B, Hq, 128, 0.5, 4)
+    for t in range(3):
+        par.step(chain.next(), 2.0, k, label=f"equal keys step {t}")
+        assert sess.topk_idx.cpu().numpy().reshape(-1).tolist() == list(range(k))
+    sess.close()
+
+
+def test_gate_equality_reuses(H):
+    """cos = 1/2 exactly against tau = 1/2 reuses ("at or above")."""
+    sess, Kb, Ksb, Vsb = H.make_session(1, 1, 1, 500, 16, "bf16")
+    a = np.zeros((1, 1, 128)); a[0, 0, :4] = 1
+    b = np.zeros((1, 1, 128)); b[0, 0, 0] = 1
+    dev = lambda x: W.round_to(x, "bf16").cuda()
+    sess.step(dev(a), 0.5, 16); sess.sync()
+    sess.step(dev(b), 0.5, 16); sess.sync()
+    assert sess.reuse_flags.item() == 1 and sess.sim.item() == 0.5
+    sess.reset()
+    sess.step(dev(a), 0.5, 16); sess.sync()
+    sess.step(dev(b), float(np.float32(0.5) + np.float32(2 ** -24) * 2), 16); sess.sync()
+    assert sess.reuse_flags.item() == 0
+    sess.close()
+
+
+def test_reset_and_rerun_are_bit_identical(H):
+    """Two runs of the same chain (with a reset between them) give identical outputs: integer
+    atomics only, no order-dependent floating-point accumulation anywhere on the path."""
+    sess, Kb, Ksb, Vsb = H.make_session(2, 8, 2, 7000, 256, "bf16")
+    outs = []
+    for rep in range(2):
+        chain = W.QueryChain(2, 8, 128, 0.95, 21)
+        rec = []
+        for t in range(12):
+            sess.step(W.round_to(chain.next(), "bf16").cuda(), 0.9, 256)
+            sess.sync()
+            rec.append((sess.out.clone(), sess.topk_idx.clone(), sess.hit_mask.clone(), sess.reuse_flags.clone(),
+                        sess.slot_idx.clone()))
+        outs.append(rec)
+        sess.reset()
+    for a, b in zip(*outs):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+    sess.close()
+
+
+def test_back_to_back_steps_without_host_sync(H):
+    """Steps enqueued without synchronising in between (the way bench.py drives them) end in the
+    same state as the same steps taken one at a time."""
+    res = []
+    for sync_each in (True, False):
+        sess, *_ = H.make_session(2, 8, 2, 7000, 256, "bf16", host_v=True)
+        chain = W.QueryChain(2, 8, 128, 0.95, 22)
+        qs = [W.round_to(chain.next(), "bf16").cuda() for _ in range(16)]
+        torch.cuda.synchronize()
+        for q in qs:
+            sess.step(q, 0.9, 256)
+            if sync_each:
+                sess.sync()
+        sess.sync()
+        res.append((sess.out.clone(), sess.topk_idx.clone(), sess.slot_idx.clone(), sess.K_slots.clone(),
+                    sess.V_slots.clone(), sess.stats()))
+        sess.close()
+    for x, y in zip(res[0][:5], res[1][:5]):
+        assert torch.equal(x, y)
+    assert res[0][5] == res[1][5]
