@@ -69,8 +69,9 @@ class Parity:
             where = f"{label} pair {p}"
             heads = slice(h * G, (h + 1) * G)
             if before.valid[p]:
-                self.min_margin = min(self.min_margin, abs(r.s_agg[p] - tau_h[h]))
-                assert abs(r.s_agg[p] - tau_h[h]) > GATE_MARGIN, f"{where}: gate too close to tau to compare"
+                if r.s_agg[p] != -1.0:   # -1 is set exactly (a non-positive cosine in the group), not computed
+                    self.min_margin = min(self.min_margin, abs(r.s_agg[p] - tau_h[h]))
+                    assert abs(r.s_agg[p] - tau_h[h]) > GATE_MARGIN, f"{where}: gate too close to tau to compare"
                 assert np.allclose(g_sim[b, heads], r.sim[b, heads], atol=2e-6), where
             assert g_reuse[p] == r.reuse_flags[p], f"{where}: reuse flag {g_reuse[p]} != {r.reuse_flags[p]}"
             assert after.valid[p] == 1, where
