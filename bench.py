@@ -93,7 +93,10 @@ def main():
     torch.cuda.synchronize()
 
     def session(flags):
-        return Q.Session(w.B, w.Hq, w.Hkv, w.N, w.k, w.dtype, K_dev, K_src, V_src, flags=flags | a.flags)
+        # the fill runs on a side stream only where it crosses PCIe; from HBM it is too short to be worth two
+        # attention launches
+        return Q.Session(w.B, w.Hq, w.Hkv, w.N, w.k, w.dtype, K_dev, K_src, V_src, flags=flags | a.flags,
+                         side_stream=(w.host_k or w.host_v))
 
     # ---- timed run: K steps after W warmup steps, overlapped fill, no events inside
     sess = session(0)
@@ -152,8 +155,8 @@ def main():
                 "score": {"bound": "hbm", "achieved": score_bytes / (us[1] * 1e-6) / 1e9 if miss_per_launch else 0.0,
                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "bytes_per_launch": score_bytes,
                           "us_per_launch": us[1], "missing_pairs_per_launch": miss_per_launch},
-                "attn": {"bound": "hbm", "achieved": attn_bytes / (us[7] * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
-                         "unit": "GB/s", "bytes_per_launch": attn_bytes, "us_per_launch": us[7]},
+                "attn": {"bound": "hbm", "achieved": attn_bytes / (us[4] * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "bytes_per_launch": attn_bytes, "us_per_launch": us[4]},
             }
 
         names, us, dd = profile(tau, W_steps, K_steps)
@@ -178,9 +181,9 @@ def main():
             per_row = 256 * (int(w.host_k) + int(w.host_v))
             for tag, uu, ddd, ns in (("fill", us, dd, K_steps), ("fill_all_miss", us2, dd2, n_all)):
                 by = per_row * ddd["slot_misses"] / ns
-                result[tag] = {"bound": "pcie", "bytes_per_launch": by, "us_per_launch": uu[6],
-                               "achieved": by / (uu[6] * 1e-6) / 1e9 if by else 0.0, "peak": peak, "unit": "GB/s",
-                               "frac": (by / (uu[6] * 1e-6) / 1e9) / peak if by else 0.0,
+                result[tag] = {"bound": "pcie", "bytes_per_launch": by, "us_per_launch": uu[3],
+                               "achieved": by / (uu[3] * 1e-6) / 1e9 if by else 0.0, "peak": peak, "unit": "GB/s",
+                               "frac": (by / (uu[3] * 1e-6) / 1e9) / peak if by else 0.0,
                                "peak_kind": "measured hipMemcpyAsync pinned H2D, 1 GiB"}
 
     # ---- the oracle on the host cores of this machine, a bounded sample of the same workload

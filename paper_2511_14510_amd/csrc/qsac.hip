@@ -17,10 +17,8 @@ using namespace qsac;
 namespace {
 
 constexpr uint32_t kMagic = 0x51534143u;  // "QSAC"
-constexpr int kStages = 9;
-const char* const kStageNames[kStages] = {"qsac_gate_kernel",      "qsac_score",       "qsac_refine_kernel<1>",
-                                          "qsac_refine_kernel<2>", "qsac_mark_kernel", "qsac_diff_kernel",
-                                          "qsac_fill_kernel",      "qsac_attn_kernel", "qsac_combine_kernel"};
+constexpr int kStages = 5;
+const char* const kStageNames[kStages] = {"gate", "score", "select", "fill", "attn"};
 
 thread_local int g_last_hip = 0;
 
@@ -81,6 +79,7 @@ void make_layout(const qsac_config* c, qsac_ws_layout* L) {
   L->stats = take(8 * 8);
   L->importance = take((size_t)c->n_q_heads * 8);
   L->sel_r = take(P * 4);
+  L->ticket = take(P * 4);
   L->total = off;
   L->n_pad = (int64_t)n_pad;
   L->words = (int32_t)words;
@@ -98,7 +97,7 @@ struct qsac_ctx {
   uint64_t steps;
   hipStream_t s_main, s_side;
   hipEvent_t ev_sel, ev_fill;
-  bool dry, overlap, profile;
+  bool dry, overlap, profile, small;
   hipEvent_t prof[kStages + 1];
   double stage_ms[kStages];
   uint64_t stage_calls;
@@ -124,6 +123,7 @@ int clear_state(qsac_ctx* c) {
   qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.valid), (size_t)c->P);
   qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.stats), (size_t)16);
   qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.miss_count), (size_t)c->P);
+  qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.ticket), (size_t)c->P);
   HIP_TRY(hipGetLastError());
   c->k_bound = 0;
   c->steps = 0;
@@ -147,24 +147,34 @@ int drain_profile(qsac_ctx* c) {
 }
 
 template <int DT, int G>
-void launch_score(const qsac_ctx* c, const qsac_step_args* a, dim3 grid, u32* keys, u32* hist) {
+void launch_score(const qsac_ctx* c, const qsac_step_args* a, u32* keys, u32* hist) {
   auto q = static_cast<const uint16_t*>(a->q);
   auto K = static_cast<const uint16_t*>(a->K_dev);
-  if (c->cfg.flags & QSAC_FLAG_SCORE_VALU)
-    qsac_score_valu_kernel<DT, G><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, c->cfg.n_q_heads,
-                                                               c->cfg.n_kv_heads, c->cfg.n_ctx, c->L.n_pad);
-  else
-    qsac_score_mfma_kernel<DT, G><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, c->cfg.n_q_heads,
-                                                               c->cfg.n_kv_heads, c->cfg.n_ctx, c->L.n_pad);
+  const int64_t N = c->cfg.n_ctx;
+  const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
+  const bool valu = (c->cfg.flags & QSAC_FLAG_SCORE_VALU) != 0;
+  if (c->small) {
+    dim3 grid((unsigned)((N + kScoreRowsSmall - 1) / kScoreRowsSmall), (unsigned)c->P);
+    if (valu)
+      qsac_score_valu_kernel<DT, G, kScoreRowsSmall, false><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad);
+    else
+      qsac_score_mfma_kernel<DT, G, kScoreRowsSmall, false><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad);
+  } else {
+    dim3 grid((unsigned)((N + kScoreRowsLarge - 1) / kScoreRowsLarge), (unsigned)c->P);
+    if (valu)
+      qsac_score_valu_kernel<DT, G, kScoreRowsLarge, true><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad);
+    else
+      qsac_score_mfma_kernel<DT, G, kScoreRowsLarge, true><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad);
+  }
 }
 
 template <int DT, int G>
-void launch_attn(const qsac_ctx* c, const qsac_step_args* a, dim3 grid, float* part_ml, float* part_acc, int rows,
-                 int which) {
+void launch_attn(const qsac_ctx* c, const qsac_step_args* a, dim3 grid, float* part_ml, float* part_acc, int* ticket,
+                 int rows, int n_splits, int which) {
   qsac_attn_kernel<DT, G><<<grid, 256, 0, c->s_main>>>(
       static_cast<const uint16_t*>(a->q), static_cast<const v4u*>(a->K_slots), static_cast<const v4u*>(a->V_slots),
-      a->reuse_flags, part_ml, part_acc, c->cfg.n_q_heads, c->cfg.n_kv_heads, a->k, c->cfg.k_max, rows,
-      c->L.max_splits, which);
+      a->reuse_flags, part_ml, part_acc, ticket, a->out, c->cfg.n_q_heads, c->cfg.n_kv_heads, a->k, c->cfg.k_max,
+      rows, n_splits, c->L.max_splits, which);
 }
 
 // Dispatch on (dtype, G) to the instantiated kernels.
@@ -229,6 +239,7 @@ int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
   c->P = cfg->batch * cfg->n_kv_heads;
   c->G = cfg->n_q_heads / cfg->n_kv_heads;
   c->dry = dry;
+  c->small = cfg->n_ctx <= kSmallMaxN;
   c->s_main = static_cast<hipStream_t>(cfg->stream_main);
   c->s_side = static_cast<hipStream_t>(cfg->stream_side);
   c->overlap = cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main && !(cfg->flags & QSAC_FLAG_SERIAL);
@@ -346,42 +357,38 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     qsac_gate_kernel<1><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
                                            a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max);
-  // 2. scores of the missing pairs (+ level-0 histogram)
+  // 2. scores of the missing pairs
   mark(1);
-  {
-    dim3 grid((unsigned)((N + kScoreRows - 1) / kScoreRows), (unsigned)P);
-    QSAC_DISPATCH(launch_score, c, a, grid, keys, hist);
-  }
-  // 3. radix select of the k-th key, bitmaps
-  dim3 sel_grid((unsigned)(L.n_pad / kSelChunk), (unsigned)P);
+  QSAC_DISPATCH(launch_score, c, a, keys, hist);
+  // 3. select the k best, diff against the cache slots
   mark(2);
-  qsac_refine_kernel<1><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
-  mark(3);
-  qsac_refine_kernel<2><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
-  mark(4);
-  qsac_mark_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, bm_new, bm_eq, bm_old, sel_r, N, L.n_pad,
-                                            L.words, k);
-  // 4. diff against the cache slots
-  mark(5);
-  qsac_diff_kernel<<<P, kDiffThreads, 0, sm>>>(a->reuse_flags, valid, bm_new, bm_eq, bm_old, sel_r, a->slot_idx,
-                                              set_sorted, a->topk_idx, a->hit_mask, miss_count, miss_slot, miss_tok,
-                                              stats, L.words, k, k_max);
-  // 5. fill the missing rows; 6. attention
+  if (c->small) {
+    qsac_select_small_kernel<<<P, kDiffThreads, 0, sm>>>(a->reuse_flags, keys, valid, a->slot_idx, set_sorted,
+                                                        a->topk_idx, a->hit_mask, miss_count, miss_slot, miss_tok,
+                                                        stats, N, L.n_pad, k, k_max);
+  } else {
+    dim3 sel_grid((unsigned)(L.n_pad / kSelChunk), (unsigned)P);
+    qsac_refine_kernel<1><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
+    qsac_refine_kernel<2><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
+    qsac_mark_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, bm_new, bm_eq, bm_old, sel_r, N, L.n_pad,
+                                              L.words, k);
+    qsac_diff_kernel<<<P, kDiffThreads, 0, sm>>>(a->reuse_flags, valid, bm_new, bm_eq, bm_old, sel_r, a->slot_idx,
+                                                set_sorted, a->topk_idx, a->hit_mask, miss_count, miss_slot,
+                                                miss_tok, stats, L.words, k, k_max);
+  }
+  // 4. fill the missing rows; 5. attention
   const int rows = attn_rows(P, k);
   const int n_splits = (k + rows - 1) / rows;
   dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
   dim3 attn_grid((unsigned)n_splits, (unsigned)P);
+  int* ticket = reinterpret_cast<int*>(ws + L.ticket);
   auto fill_on = [&](hipStream_t s) {
     qsac_fill_kernel<<<fill_grid, 256, 0, s>>>(miss_count, miss_slot, miss_tok, static_cast<const v4u*>(a->K_src),
                                                static_cast<const v4u*>(a->V_src), static_cast<v4u*>(a->K_slots),
                                                static_cast<v4u*>(a->V_slots), N, k_max);
   };
   auto attend = [&](int which) {
-    QSAC_DISPATCH(launch_attn, c, a, attn_grid, part_ml, part_acc, rows, which);
-  };
-  auto combine = [&](int which) {
-    qsac_combine_kernel<<<P * G, 128, 0, sm>>>(part_ml, part_acc, a->reuse_flags, a->out, Hq, Hkv, G, n_splits,
-                                               L.max_splits, which);
+    QSAC_DISPATCH(launch_attn, c, a, attn_grid, part_ml, part_acc, ticket, rows, n_splits, which);
   };
   if (c->overlap) {
     // the fill runs on the side stream while the pairs that reused their cache are attended to
@@ -392,15 +399,12 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     attend(1);
     HIP_TRY(hipStreamWaitEvent(sm, c->ev_fill, 0));
     attend(2);
-    combine(0);
   } else {
-    mark(6);
+    mark(3);
     fill_on(sm);
-    mark(7);
+    mark(4);
     attend(0);
-    mark(8);
-    combine(0);
-    mark(9);
+    mark(5);
     c->prof_pending = c->profile;
   }
   HIP_TRY(hipGetLastError());

@@ -5,15 +5,16 @@
 //   gate     cache lookup: CosSim (Section 3.1) per query head in fp64, Eq. (2) per KV head,
 //            label update q_c <- q_t on a miss (the paper fuses the two as well, Section 6.2)
 //   score    Eq. (1) for the head's query group against all N keys, S[n] = max_g q_g.k_n,
-//            stored as order-preserving 32-bit keys, with the first radix histogram fused in
-//   refine1, refine2, mark
-//            radix select of the k-th largest key (11 + 11 + 10 bits), then bitmaps of the
-//            keys above it and equal to it
-//   diff     ties by lowest index, ascending index list, hit mask against the cached tokens,
-//            (slot, token) miss list, slot table update
+//            stored as order-preserving 32-bit keys
+//   select   radix select of the k-th largest key (11 + 11 + 10 bits), ties by lowest index,
+//            ascending index list, hit mask against the cached tokens, (slot, token) miss
+//            list, slot table update.  Up to kSmallMaxN keys: one workgroup per pair does all
+//            of it with its bitmaps in LDS.  Beyond: the first histogram is fused into the
+//            scoring kernel and the levels run as grid-wide kernels (refine1, refine2, mark,
+//            diff) so that a few pairs with very long contexts still fill the chip.
 //   fill     copies the missing K / V rows from the fill sources into the slots
-//   attn     softmax(q K_c^T / sqrt(d)) V_c over the slots (Section 2.1), split over slots
-//   combine  merges the splits
+//   attn     softmax(q K_c^T / sqrt(d)) V_c over the slots (Section 2.1), split over slots;
+//            the last workgroup of a pair to finish merges the splits
 //
 // Pairs whose gate reused the cache leave every miss-path kernel at once.
 #pragma once
@@ -28,7 +29,10 @@ typedef unsigned long long u64;
 constexpr int kD = 128;            // head_dim
 constexpr int kRowU4 = 16;         // 16-byte chunks per 256-byte row
 constexpr int kBins = 2048;        // bins per radix level (level 2 uses the first 1024)
-constexpr int kScoreRows = 1024;   // keys per workgroup of the scoring kernel
+constexpr int kScoreRowsSmall = 256;   // keys per workgroup of the scoring kernel (small-N path)
+constexpr int kScoreRowsLarge = 1024;  // ... when the level-0 histogram is fused in (large-N path)
+constexpr int kSmallMaxN = 131072;     // largest N whose three bitmaps fit in LDS (3 x 16 KiB)
+constexpr int kTilePitch = 272;        // bytes between key rows of an LDS tile: 256 + 16 keeps b128 reads conflict-free
 constexpr int kSelChunk = 8192;    // keys per workgroup of the select passes
 constexpr int kFillRows = 64;      // miss-list entries per workgroup of the fill kernel
 constexpr int kDiffThreads = 1024;
@@ -126,10 +130,12 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* s_wave /*[NW+1]*
 }
 
 // Among bins [0, nbins) of `hist`, finds the bin b with  count(bins > b) < need <= count(bins >= b).
-// Returns b; *above = count(bins > b).  256 threads; contains barriers.
-__device__ __forceinline__ int find_bin(const u32* __restrict__ hist, int nbins, int need, int* above,
-                                        int* s_wave, int* s_res) {
-  const int per = nbins / 256;  // 8 or 4
+// Returns b; *above = count(bins > b).  NT threads (nbins is a multiple of NT, at most 8 bins per
+// thread); contains barriers.
+template <int NT>
+__device__ __forceinline__ int find_bin(const u32* hist, int nbins, int need, int* above, int* s_wave,
+                                        int* s_res) {
+  const int per = nbins / NT;
   // thread t owns bins [hi - per + 1, hi] counted from the top: t = 0 owns the highest bins
   const int hi = nbins - 1 - (int)threadIdx.x * per;
   int c[8];
@@ -144,7 +150,7 @@ __device__ __forceinline__ int find_bin(const u32* __restrict__ hist, int nbins,
     s_res[1] = 0;
   }
   int tot;
-  int before = block_exclusive_scan<4>(local, s_wave, &tot);  // keys in bins above this thread's
+  int before = block_exclusive_scan<NT / 64>(local, s_wave, &tot);  // keys in bins above this thread's
   if (before < need && need <= before + local) {
     int run = before;
 #pragma unroll
@@ -240,9 +246,10 @@ __global__ __launch_bounds__(256) void qsac_gate_kernel(
 
 // ---------------------------------------------------------------- score
 
-// After the key tile of a workgroup sits in LDS: write it out and add it to the level-0 histogram.
-__device__ __forceinline__ void score_epilogue(const u32* s_keys, u32* s_hist, u32* __restrict__ keys_p,
-                                               u32* __restrict__ hist_p, int64_t row0, int64_t N) {
+// Large-N path only: after the key tile of a workgroup sits in LDS, write it out and add it to
+// the pair's level-0 histogram.
+__device__ __forceinline__ void score_hist_epilogue(const u32* s_keys, u32* s_hist, u32* __restrict__ keys_p,
+                                                    u32* __restrict__ hist_p, int64_t row0, int64_t N) {
   __syncthreads();
   const int t4 = threadIdx.x * 4;
   v4u kk = *reinterpret_cast<const v4u*>(s_keys + t4);
@@ -259,21 +266,28 @@ __device__ __forceinline__ void score_epilogue(const u32* s_keys, u32* s_hist, u
   }
 }
 
-// MFMA form.  Per wave and iteration a 16 x 128 tile of K meets the (zero-padded to 16) query
-// group in four v_mfma_f32_16x16x32: the query group is the A operand (row = query), the keys
-// are the B operand (column = key).  Lane l reads 64 contiguous bytes of key row l%16 (quarter
-// l/16 of the row); MFMA j contracts the j-th 16-byte piece of every quarter, and the query
-// fragments are cut the same way, so the products pair up correctly whatever order the
-// hardware sums them in.  acc[i] of lane l is the score of query 4*(l/16)+i against key l%16.
-template <int DT, int G>
+// MFMA form.  Per wave and 16-key tile, the 16 x 128 block of K meets the query group (zero
+// padded to 16 rows) in four v_mfma_f32_16x16x32: queries are the A operand (row = query),
+// keys the B operand (column = key); acc[i] of lane l is the score of query 4*(l/16)+i against
+// key l%16.  The B operand wants lane l to hold pieces of key row l%16, which read straight
+// from HBM costs half the bandwidth (every load instruction touches 32 cache lines for 1 KiB).
+// So each wave reads its tile with four fully coalesced 1-KiB loads (lane l: 16 bytes at
+// l*16), parks it in a wave-private LDS tile with a 272-byte row pitch, and reads the operand
+// layout back from there, conflict-free.  Sixteen global loads per lane are in flight before
+// the first tile is consumed.  Both operands are cut into the same 8-element pieces, so the
+// products pair up correctly whatever order the hardware sums them in.
+// ROWS keys per workgroup (four waves, ROWS/4 each).  HIST fuses the level-0 histogram.
+template <int DT, int G, int ROWS, bool HIST>
 __global__ __launch_bounds__(256) void qsac_score_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint8_t* __restrict__ reuse_flags,
     u32* __restrict__ keys, u32* __restrict__ hist, int Hq, int Hkv, int64_t N, int64_t n_pad) {
   const int p = blockIdx.y;
   if (reuse_flags[p]) return;
-  __shared__ u32 s_hist[kBins];
-  __shared__ __attribute__((aligned(16))) u32 s_keys[kScoreRows];
-  for (int i = threadIdx.x; i < kBins; i += 256) s_hist[i] = 0;
+  __shared__ __attribute__((aligned(16))) unsigned char s_tile[4][2][16 * kTilePitch];
+  __shared__ u32 s_hist[HIST ? kBins : 1];
+  __shared__ __attribute__((aligned(16))) u32 s_keys[HIST ? ROWS : 4];
+  if (HIST)
+    for (int i = threadIdx.x; i < kBins; i += 256) s_hist[i] = 0;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = lane & 15, quarter = lane >> 4;
@@ -283,55 +297,72 @@ __global__ __launch_bounds__(256) void qsac_score_mfma_kernel(
 #pragma unroll
   for (int j = 0; j < 4; ++j) qa[j] = (m < G) ? qg[m * kRowU4 + quarter * 4 + j] : v4u{0, 0, 0, 0};
 
-  const int64_t row0 = (int64_t)blockIdx.x * kScoreRows;
+  const int64_t row0 = (int64_t)blockIdx.x * ROWS;
   const v4u* Kp = reinterpret_cast<const v4u*>(K + (size_t)p * (size_t)N * kD);
-  const int wrow = wave * (kScoreRows / 4);
+  constexpr int WROWS = ROWS / 4;
+  const int wrow = wave * WROWS;
+  u32* kout = keys + (size_t)p * n_pad + row0;
+  const int64_t last = N - 1;
 
-  for (int it = 0; it < kScoreRows / 4 / 16; it += 4) {
-    v4u kb[4][4];
+  for (int t0 = 0; t0 < WROWS / 16; t0 += 4) {
+    v4u g[4][4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      int64_t n = row0 + wrow + (it + u) * 16 + m;
-      n = n < N ? n : N - 1;
-      const v4u* src = Kp + n * kRowU4 + quarter * 4;
+      const int64_t tile_row = row0 + wrow + (t0 + u) * 16;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) kb[u][j] = __builtin_nontemporal_load(src + j);
+      for (int j = 0; j < 4; ++j) {
+        int64_t n = tile_row + 4 * j + quarter;  // lane l: row 4j + l/16 of the tile, piece l%16
+        n = n < last ? n : last;
+        g[u][j] = __builtin_nontemporal_load(Kp + n * kRowU4 + m);
+      }
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
+      unsigned char* tile = s_tile[wave][u & 1];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        *reinterpret_cast<v4u*>(tile + (4 * j + quarter) * kTilePitch + m * 16) = g[u][j];
       f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc = mfma16<DT>(qa[j], kb[u][j], acc);
+      for (int j = 0; j < 4; ++j) {
+        const v4u kb = *reinterpret_cast<const v4u*>(tile + m * kTilePitch + (quarter * 4 + j) * 16);
+        acc = mfma16<DT>(qa[j], kb, acc);
+      }
       // lanes 0-15 hold queries 0-3, lanes 16-31 queries 4-7 (rows >= G are zero padding)
       float s = acc[0];
 #pragma unroll
-      for (int i = 1; i < 4; ++i) {
-        const int gq = quarter * 4 + i;  // query this register belongs to
-        if (gq < G) s = fmaxf(s, acc[i]);
-      }
+      for (int i = 1; i < 4; ++i)
+        if (quarter * 4 + i < G) s = fmaxf(s, acc[i]);
       if (G > 4) {
-        float t = __shfl_down(s, 16);  // lane 16+m -> lane m
+        const float t = __shfl_down(s, 16);  // lane 16+m -> lane m
         s = fmaxf(s, t);
       }
-      const int r = wrow + (it + u) * 16 + m;
-      if (quarter == 0) s_keys[r] = (row0 + r < N) ? ordered_key(s) : 0u;
+      const int r = wrow + (t0 + u) * 16 + m;
+      const u32 key = (row0 + r < N) ? ordered_key(s) : 0u;
+      if (quarter == 0) {
+        if (HIST)
+          s_keys[r] = key;
+        else
+          kout[r] = key;
+      }
     }
   }
-  score_epilogue(s_keys, s_hist, keys + (size_t)p * n_pad, hist + (size_t)p * 3 * kBins, row0, N);
+  if (HIST) score_hist_epilogue(s_keys, s_hist, keys + (size_t)p * n_pad, hist + (size_t)p * 3 * kBins, row0, N);
 }
 
 // Vector-ALU form.  A 16-lane DPP row takes one key row (16 bytes per lane), four rows per
-// wave-wide load; each lane forms G partial dot products with v_dot2 and the row sums them
-// through DPP.  Group r of the wave handles rows 4r..4r+3 of each 16-row tile.
-template <int DT, int G>
+// wave-wide load, fully coalesced; each lane forms G partial dot products with v_dot2 and the
+// row sums them through DPP.  Row group r of the wave handles rows 4r..4r+3 of each 16-key tile.
+template <int DT, int G, int ROWS, bool HIST>
 __global__ __launch_bounds__(256) void qsac_score_valu_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint8_t* __restrict__ reuse_flags,
     u32* __restrict__ keys, u32* __restrict__ hist, int Hq, int Hkv, int64_t N, int64_t n_pad) {
   const int p = blockIdx.y;
   if (reuse_flags[p]) return;
-  __shared__ u32 s_hist[kBins];
-  __shared__ __attribute__((aligned(16))) u32 s_keys[kScoreRows];
-  for (int i = threadIdx.x; i < kBins; i += 256) s_hist[i] = 0;
+  __shared__ u32 s_hist[HIST ? kBins : 1];
+  __shared__ __attribute__((aligned(16))) u32 s_keys[HIST ? ROWS : 4];
+  if (HIST)
+    for (int i = threadIdx.x; i < kBins; i += 256) s_hist[i] = 0;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, r = lane >> 4;
@@ -341,30 +372,41 @@ __global__ __launch_bounds__(256) void qsac_score_valu_kernel(
 #pragma unroll
   for (int g = 0; g < G; ++g) qf[g] = qg[g * kRowU4 + c];
 
-  const int64_t row0 = (int64_t)blockIdx.x * kScoreRows;
+  const int64_t row0 = (int64_t)blockIdx.x * ROWS;
   const v4u* Kp = reinterpret_cast<const v4u*>(K + (size_t)p * (size_t)N * kD);
-  const int wrow = wave * (kScoreRows / 4);
+  constexpr int WROWS = ROWS / 4;
+  const int wrow = wave * WROWS;
+  u32* kout = keys + (size_t)p * n_pad + row0;
+  const int64_t last = N - 1;
 
-  for (int it = 0; it < kScoreRows / 4 / 16; ++it) {
-    v4u kv[4];
+  for (int t0 = 0; t0 < WROWS / 16; t0 += 2) {
+    v4u kv[2][4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      int64_t n = row0 + wrow + it * 16 + r * 4 + u;
-      n = n < N ? n : N - 1;
-      kv[u] = __builtin_nontemporal_load(Kp + n * kRowU4 + c);
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        int64_t n = row0 + wrow + (t0 + t) * 16 + r * 4 + u;
+        n = n < last ? n : last;
+        kv[t][u] = __builtin_nontemporal_load(Kp + n * kRowU4 + c);
+      }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      u32 out[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float best = row16_sum(dot8<DT>(qf[0], kv[t][u]));
+#pragma unroll
+        for (int g = 1; g < G; ++g) best = fmaxf(best, row16_sum(dot8<DT>(qf[g], kv[t][u])));
+        const int rr = wrow + (t0 + t) * 16 + r * 4 + u;
+        out[u] = (row0 + rr < N) ? ordered_key(best) : 0u;
+      }
+      if (c == 0) {
+        u32* dst = (HIST ? s_keys : kout) + wrow + (t0 + t) * 16 + r * 4;
+        *reinterpret_cast<v4u*>(dst) = v4u{out[0], out[1], out[2], out[3]};
+      }
     }
-    u32 out[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      float best = row16_sum(dot8<DT>(qf[0], kv[u]));
-#pragma unroll
-      for (int g = 1; g < G; ++g) best = fmaxf(best, row16_sum(dot8<DT>(qf[g], kv[u])));
-      const int rr = wrow + it * 16 + r * 4 + u;
-      out[u] = (row0 + rr < N) ? ordered_key(best) : 0u;
-    }
-    if (c == 0) *reinterpret_cast<v4u*>(s_keys + wrow + it * 16 + r * 4) = v4u{out[0], out[1], out[2], out[3]};
   }
-  score_epilogue(s_keys, s_hist, keys + (size_t)p * n_pad, hist + (size_t)p * 3 * kBins, row0, N);
+  if (HIST) score_hist_epilogue(s_keys, s_hist, keys + (size_t)p * n_pad, hist + (size_t)p * 3 * kBins, row0, N);
 }
 
 // ---------------------------------------------------------------- radix select
@@ -386,11 +428,11 @@ __global__ __launch_bounds__(256) void qsac_refine_kernel(const uint8_t* __restr
   for (int i = threadIdx.x; i < kBins; i += 256) s_hist[i] = 0;
   int above;
   int need = k;
-  u32 prefix = (u32)find_bin(hp, kBins, need, &above, s_wave, s_res);
+  u32 prefix = (u32)find_bin<256>(hp, kBins, need, &above, s_wave, s_res);
   need -= above;
   int shift = 21;
   if (LEVEL == 2) {
-    u32 b1 = (u32)find_bin(hp + kBins, kBins, need, &above, s_wave, s_res);
+    u32 b1 = (u32)find_bin<256>(hp + kBins, kBins, need, &above, s_wave, s_res);
     prefix = (prefix << 11) | b1;
     shift = 10;
   }
@@ -429,11 +471,11 @@ __global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restric
   __shared__ int s_res[2];
   const u32* hp = hist + (size_t)p * 3 * kBins;
   int above, need = k;
-  u32 b0 = (u32)find_bin(hp, kBins, need, &above, s_wave, s_res);
+  u32 b0 = (u32)find_bin<256>(hp, kBins, need, &above, s_wave, s_res);
   need -= above;
-  u32 b1 = (u32)find_bin(hp + kBins, kBins, need, &above, s_wave, s_res);
+  u32 b1 = (u32)find_bin<256>(hp + kBins, kBins, need, &above, s_wave, s_res);
   need -= above;
-  u32 b2 = (u32)find_bin(hp + 2 * kBins, 1024, need, &above, s_wave, s_res);
+  u32 b2 = (u32)find_bin<256>(hp + 2 * kBins, 1024, need, &above, s_wave, s_res);
   need -= above;  // number of keys equal to T that belong to the set (>= 1)
   const u32 T = (b0 << 21) | (b1 << 10) | b2;
   if (blockIdx.x == 0 && threadIdx.x == 0) sel_r[p] = need;
@@ -466,36 +508,28 @@ __global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restric
 
 // ---------------------------------------------------------------- diff
 
-// One workgroup (1024 threads) per missing pair; thread t owns a contiguous run of bitmap words.
-//  A. ties: of the keys equal to T, the r with the lowest indices join the set;
+// Shared by the one-workgroup select (bitmaps in LDS) and the large-N diff kernel (bitmaps in
+// the workspace).  Thread t of NT owns a contiguous run of bitmap words.  nw holds the keys above
+// the k-th key on entry and the selected set on exit.
+//  A. ties: of the keys equal to the k-th key, the r with the lowest indices join the set;
 //  B. bitmap of the tokens cached before the step (from slot_idx);
 //  C. ascending index list, hit mask, ascending list of tokens to fetch;
 //  D. ascending list of slots whose token left the set;
-//  E. i-th such slot takes the i-th token to fetch.
-__global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
-    const uint8_t* __restrict__ reuse_flags, u32* __restrict__ valid, u32* __restrict__ bm_new,
-    const u32* __restrict__ bm_eq, u32* __restrict__ bm_old, const int* __restrict__ sel_r,
-    int* __restrict__ slot_idx, int* __restrict__ set_sorted, int* __restrict__ topk_idx,
-    uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count, int* __restrict__ miss_slot,
-    int* __restrict__ miss_tok, u64* __restrict__ stats, int words, int k, int k_max) {
-  const int p = blockIdx.x;
-  if (reuse_flags[p]) return;
-  __shared__ int s_wave[17];
+//  E. the i-th such slot takes the i-th token to fetch.
+template <int NT>
+__device__ __forceinline__ void diff_phases(u32* nw, const u32* eq, u32* old, bool was_valid, int r, int words,
+                                            int k, int* __restrict__ sl, int* __restrict__ ss,
+                                            int* __restrict__ tk, uint8_t* __restrict__ hm, int* __restrict__ ms,
+                                            int* __restrict__ mt, int* __restrict__ miss_count_p,
+                                            u32* __restrict__ valid_p, u64* __restrict__ stats, int* s_wave) {
   const int tid = threadIdx.x;
-  u32* nw = bm_new + (size_t)p * words;
-  const u32* eq = bm_eq + (size_t)p * words;
-  u32* old = bm_old + (size_t)p * words;
-  int* sl = slot_idx + (size_t)p * k_max;
-  const bool was_valid = valid[p] != 0;
-  const int r = sel_r[p];
-  const int wpt = (words + kDiffThreads - 1) / kDiffThreads;
+  const int wpt = (words + NT - 1) / NT;
   const int w0 = min(tid * wpt, words), w1 = min(w0 + wpt, words);
   int total;
-
   // A
   int ceq = 0;
   for (int w = w0; w < w1; ++w) ceq += __popc(eq[w]);
-  int rank = block_exclusive_scan<16>(ceq, s_wave, &total);
+  int rank = block_exclusive_scan<NT / 64>(ceq, s_wave, &total);
   for (int w = w0; w < w1; ++w) {
     u32 e = eq[w];
     const int c = __popc(e);
@@ -515,7 +549,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
   }
   // B
   if (was_valid)
-    for (int j = tid; j < k; j += kDiffThreads) {
+    for (int j = tid; j < k; j += NT) {
       const int tok = sl[j];
       atomicOr(&old[tok >> 5], 1u << (tok & 31));
     }
@@ -527,13 +561,8 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
     cn += __popc(a);
     cm += __popc(a & ~o);
   }
-  int jn = block_exclusive_scan<16>(cn, s_wave, &total);
-  int jm = block_exclusive_scan<16>(cm, s_wave, &total);
-  int* tk = topk_idx + (size_t)p * k;
-  uint8_t* hm = hit_mask + (size_t)p * k;
-  int* ss = set_sorted + (size_t)p * k_max;
-  int* mt = miss_tok + (size_t)p * k_max;
-  int* ms = miss_slot + (size_t)p * k_max;
+  int jn = block_exclusive_scan<NT / 64>(cn, s_wave, &total);
+  int jm = block_exclusive_scan<NT / 64>(cm, s_wave, &total);
   for (int w = w0; w < w1; ++w) {
     u32 a = nw[w];
     const u32 o = old[w];
@@ -555,7 +584,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
     }
   }
   // D
-  const int spt = (k + kDiffThreads - 1) / kDiffThreads;
+  const int spt = (k + NT - 1) / NT;
   const int j0 = min(tid * spt, k), j1 = min(j0 + spt, k);
   int ce = 0;
   for (int j = j0; j < j1; ++j) {
@@ -566,7 +595,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
     }
     ce += ev;
   }
-  int je = block_exclusive_scan<16>(ce, s_wave, &total);
+  int je = block_exclusive_scan<NT / 64>(ce, s_wave, &total);
   const int m = total;
   for (int j = j0; j < j1; ++j) {
     bool ev = true;
@@ -578,13 +607,105 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
   }
   __syncthreads();
   // E
-  for (int i = tid; i < m; i += kDiffThreads) sl[ms[i]] = mt[i];
+  for (int i = tid; i < m; i += NT) sl[ms[i]] = mt[i];
   if (tid == 0) {
-    miss_count[p] = m;
-    valid[p] = 1;
+    *miss_count_p = m;
+    *valid_p = 1;
     atomicAdd(&stats[3], (u64)(k - m));
     atomicAdd(&stats[4], (u64)m);
   }
+}
+
+// Large-N path: one workgroup per missing pair, bitmaps in the workspace (made by qsac_mark_kernel).
+__global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
+    const uint8_t* __restrict__ reuse_flags, u32* __restrict__ valid, u32* __restrict__ bm_new,
+    const u32* __restrict__ bm_eq, u32* __restrict__ bm_old, const int* __restrict__ sel_r,
+    int* __restrict__ slot_idx, int* __restrict__ set_sorted, int* __restrict__ topk_idx,
+    uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count, int* __restrict__ miss_slot,
+    int* __restrict__ miss_tok, u64* __restrict__ stats, int words, int k, int k_max) {
+  const int p = blockIdx.x;
+  if (reuse_flags[p]) return;
+  __shared__ int s_wave[17];
+  diff_phases<kDiffThreads>(bm_new + (size_t)p * words, bm_eq + (size_t)p * words, bm_old + (size_t)p * words,
+                            valid[p] != 0, sel_r[p], words, k, slot_idx + (size_t)p * k_max,
+                            set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
+                            miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max, miss_count + p, valid + p,
+                            stats, s_wave);
+}
+
+// Small-N path (N <= kSmallMaxN): one workgroup of 1024 threads per missing pair selects and
+// diffs in one go.  The pair's keys (4N bytes, just written by the scoring kernel) are read
+// four times from L2: three histogram passes (11 + 11 + 10 bits) that pin the k-th largest key
+// T exactly, one pass that ballots "key > T" and "key == T" into LDS bitmaps.
+__global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
+    const uint8_t* __restrict__ reuse_flags, const u32* __restrict__ keys, u32* __restrict__ valid,
+    int* __restrict__ slot_idx, int* __restrict__ set_sorted, int* __restrict__ topk_idx,
+    uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count, int* __restrict__ miss_slot,
+    int* __restrict__ miss_tok, u64* __restrict__ stats, int64_t N, int64_t n_pad, int k, int k_max) {
+  const int p = blockIdx.x;
+  if (reuse_flags[p]) return;
+  constexpr int NT = kDiffThreads;
+  __shared__ u32 s_hist[kBins];
+  __shared__ u32 s_new[kSmallMaxN / 32], s_eq[kSmallMaxN / 32], s_old[kSmallMaxN / 32];
+  __shared__ int s_wave[17];
+  __shared__ int s_res[2];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const u32* kp = keys + (size_t)p * n_pad;
+  const v4u* kp4 = reinterpret_cast<const v4u*>(kp);
+  const int n = (int)N;
+  const int nvec = (n + 3) >> 2;  // n_pad is a multiple of 8192, so whole vectors can be read
+
+  int need = k, above;
+  u32 prefix = 0;
+  // level 0: bits 31..21; level 1: bits 20..10 under the level-0 bin; level 2: bits 9..0
+#pragma unroll
+  for (int level = 0; level < 3; ++level) {
+    const int shift = level == 1 ? 21 : 10;  // from level 1 on, key >> shift must equal prefix
+    const int sub = level == 0 ? 21 : (level == 1 ? 10 : 0);
+    const u32 mask = level == 2 ? 0x3ffu : 0x7ffu;
+    for (int i = tid; i < kBins; i += NT) s_hist[i] = 0;
+    __syncthreads();
+    for (int v = tid; v < nvec; v += NT) {
+      const v4u kk = kp4[v];
+      const int e = v * 4;
+      const u32 ks[4] = {kk.x, kk.y, kk.z, kk.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool match = level == 0 || (ks[i] >> shift) == prefix;
+        if (e + i < n && match) atomicAdd(&s_hist[(ks[i] >> sub) & mask], 1u);
+      }
+    }
+    __syncthreads();
+    const int nb = level == 2 ? 1024 : kBins;
+    const u32 b = (u32)find_bin<NT>(s_hist, nb, need, &above, s_wave, s_res);
+    need -= above;
+    prefix = level == 0 ? b : (prefix << (level == 1 ? 11 : 10)) | b;
+  }
+  const u32 T = prefix;   // the k-th largest key; `need` of the keys equal to it belong to the set
+  const int words = (n + 31) >> 5;
+  const int n64 = (n + 63) & ~63;
+  for (int base = (tid >> 6) * 64; base < n64; base += NT) {
+    const int e = base + lane;
+    const bool in = e < n;
+    const u32 key = in ? kp[e] : 0u;
+    const u64 mg = __ballot(in && key > T);
+    const u64 me = __ballot(in && key == T);
+    const int w = e >> 5;
+    if (lane == 0) {
+      s_new[w] = (u32)mg;
+      s_eq[w] = (u32)me;
+      s_old[w] = 0;
+    } else if (lane == 32) {
+      s_new[w] = (u32)(mg >> 32);
+      s_eq[w] = (u32)(me >> 32);
+      s_old[w] = 0;
+    }
+  }
+  __syncthreads();
+  diff_phases<NT>(s_new, s_eq, s_old, valid[p] != 0, need, words, k, slot_idx + (size_t)p * k_max,
+                  set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
+                  miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max, miss_count + p, valid + p, stats,
+                  s_wave);
 }
 
 // ---------------------------------------------------------------- fill
@@ -643,12 +764,14 @@ __device__ __forceinline__ bool pair_selected(int which, const uint8_t* reuse_fl
 // its lanes form the G dot products with v_dot2, sum them over the row, and every lane keeps
 // its own online-softmax state (running max, sum, 8 output channels per head) for the slots of
 // its row group.  Tiles of 16 slots per wave share one rescale.  Row groups, then waves, are
-// merged at the end; the split's (max, sum, unnormalised output) goes to the workspace.
+// merged at the end; the split's (max, sum, unnormalised output) goes to the workspace and the
+// last workgroup of the pair to finish merges the splits and writes the output.
 template <int DT, int G>
 __global__ __launch_bounds__(256) void qsac_attn_kernel(
     const uint16_t* __restrict__ q, const v4u* __restrict__ K_slots, const v4u* __restrict__ V_slots,
-    const uint8_t* __restrict__ reuse_flags, float* __restrict__ part_ml, float* __restrict__ part_acc, int Hq,
-    int Hkv, int k, int k_max, int rows, int max_splits, int which) {
+    const uint8_t* __restrict__ reuse_flags, float* __restrict__ part_ml, float* __restrict__ part_acc,
+    int* __restrict__ ticket, float* __restrict__ out, int Hq, int Hkv, int k, int k_max, int rows, int n_splits,
+    int max_splits, int which) {
   const int p = blockIdx.y, split = blockIdx.x;
   if (!pair_selected(which, reuse_flags, p)) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -747,6 +870,7 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
   // merge the four waves through LDS
   __shared__ float s_ml[4][G][2];
   __shared__ float s_acc[4][G][kD];
+  __shared__ int s_last;
   if (r == 0) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -759,6 +883,8 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
     }
   }
   __syncthreads();
+  const int b_out = p / Hkv, h_out = p % Hkv;
+  float* out_p = out + ((size_t)b_out * Hq + (size_t)h_out * G) * kD;
   for (int i = threadIdx.x; i < G * kD; i += 256) {
     const int g = i >> 7, d = i & 127;
     float M = kNegInf;
@@ -772,39 +898,45 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
       L += s_ml[w][g][1] * wt;
       A += s_acc[w][g][d] * wt;
     }
-    const size_t slot = ((size_t)p * G + g) * max_splits + split;
-    part_acc[slot * kD + d] = A;
-    if (d == 0) {
-      part_ml[slot * 2 + 0] = M;
-      part_ml[slot * 2 + 1] = L;
+    if (n_splits == 1) {
+      out_p[i] = A / L;
+    } else {
+      const size_t slot = ((size_t)p * G + g) * max_splits + split;
+      part_acc[slot * kD + d] = A;
+      if (d == 0) {
+        part_ml[slot * 2 + 0] = M;
+        part_ml[slot * 2 + 1] = L;
+      }
     }
   }
-}
-
-// One workgroup of 128 threads per query head: merges the splits and normalises.
-__global__ __launch_bounds__(128) void qsac_combine_kernel(const float* __restrict__ part_ml,
-                                                           const float* __restrict__ part_acc,
-                                                           const uint8_t* __restrict__ reuse_flags,
-                                                           float* __restrict__ out, int Hq, int Hkv, int G,
-                                                           int n_splits, int max_splits, int which) {
-  const int pg = blockIdx.x;  // p * G + g
-  const int p = pg / G, g = pg % G;
-  if (!pair_selected(which, reuse_flags, p)) return;
-  const int d = threadIdx.x;
-  const float kNegInf = -__builtin_inff();
-  const float* ml = part_ml + (size_t)pg * max_splits * 2;
-  const float* pa = part_acc + (size_t)pg * max_splits * kD;
-  float M = kNegInf;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml[s * 2]);
-  float L = 0.f, A = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const float ms = ml[s * 2];
-    const float wt = (ms == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
-    L += ml[s * 2 + 1] * wt;
-    A += pa[(size_t)s * kD + d] * wt;
+  if (n_splits == 1) return;
+  // The last workgroup of the pair to get here merges the splits (in split order, so the result
+  // does not depend on which one that is).
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int t = atomicAdd(&ticket[p], 1);
+    s_last = (t == n_splits - 1);
   }
-  const int b = p / Hkv, h = p % Hkv;
-  out[((size_t)b * Hq + (size_t)h * G + g) * kD + d] = A / L;
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  for (int i = threadIdx.x; i < G * kD; i += 256) {
+    const int g = i >> 7, d = i & 127;
+    const float* ml = part_ml + ((size_t)p * G + g) * max_splits * 2;
+    const float* pa = part_acc + ((size_t)p * G + g) * max_splits * kD;
+    float M = kNegInf;
+    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml[s * 2]);
+    float L = 0.f, A = 0.f;
+    for (int s = 0; s < n_splits; ++s) {
+      const float ms = ml[s * 2];
+      const float wt = (ms == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+      L += ml[s * 2 + 1] * wt;
+      A += pa[(size_t)s * kD + d] * wt;
+    }
+    out_p[i] = A / L;
+  }
+  if (threadIdx.x == 0) ticket[p] = 0;  // ready for the next launch
 }
 
 // Clears `n` 32-bit words (used instead of a memset node so that the step can be captured in a graph).

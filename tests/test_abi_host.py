@@ -50,7 +50,7 @@ def test_workspace_size_and_layout(lib):
     L = Q.qsac_workspace_layout(cfg)
     assert n == L.total and n > 64 * 32768 * 4
     assert L.n_pad == 32768 and L.words == 1024 and L.max_splits == 32
-    offs = [getattr(L, f) for f, _ in Q.qsac_ws_layout._fields_[:15]]
+    offs = [getattr(L, f) for f, _ in Q.qsac_ws_layout._fields_[:16]]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     cfg = Q.make_config(1, 8, 2, 5000, 100, Q.QSAC_F16)
     assert Q.qsac_workspace_layout(cfg).n_pad == 8192
@@ -140,8 +140,8 @@ def test_strerror_and_stage_names(lib):
         assert Q.qsac_strerror(code) != "unknown error"
     assert Q.qsac_strerror(-99) == "unknown error"
     n = lib.qsac_num_stages()
-    assert n == 9 and lib.qsac_stage_name(n) is None
-    assert lib.qsac_stage_name(0) == b"qsac_gate_kernel" and lib.qsac_stage_name(7) == b"qsac_attn_kernel"
+    assert n == 5 and lib.qsac_stage_name(n) is None
+    assert [lib.qsac_stage_name(i) for i in range(n)] == [b"gate", b"score", b"select", b"fill", b"attn"]
 
 
 def test_binding_has_no_cpu_fallback():

@@ -101,6 +101,16 @@ def test_many_pairs_long_rows(H):
     run_chain(H, B=8, Hq=16, Hkv=4, N=20000, k=640, k_max=640, dtype="bf16", steps=6)
 
 
+@pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_SCORE_VALU])
+def test_large_n_path(H, flags):
+    """N above 131072 takes the grid-wide select (histogram fused into scoring, refine, mark, diff)."""
+    run_chain(H, B=1, Hq=8, Hkv=2, N=140001, k=700, k_max=700, dtype="bf16", steps=6, flags=flags, tau=0.93)
+
+
+def test_small_path_at_its_largest_n(H):
+    run_chain(H, B=1, Hq=5, Hkv=1, N=131072, k=1000, k_max=1000, dtype="bf16", steps=4, tau=0.93, expect_both=False)
+
+
 def exact_tie_case(H, flags):
     """K entries in {-1, 0, 1} and queries with a few small-integer entries: every score is a small
     integer, exact in fp32 and fp64 alike, with hundreds of exact ties across the k-th score - the
