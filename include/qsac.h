@@ -100,7 +100,6 @@ typedef struct {
   size_t stats;      /* u64 [8]              cumulative counters                                          */
   size_t importance; /* f64 [n_q_heads]      Eq. (2) weights                                              */
   size_t sel_r;      /* i32 [P]              keys equal to the k-th key that belong to the set (last miss)        */
-  size_t ticket;     /* i32 [P]              attention splits of the pair that have finished (0 between launches) */
   size_t total;      /* bytes needed                                                                      */
   int64_t n_pad;     /* N rounded up to the select chunk                                                  */
   int32_t words;     /* 32-bit words per bitmap                                                           */
@@ -180,7 +179,7 @@ int qsac_last_hip_error(void);
  * order, are: 0 "gate" (qsac_gate_kernel), 1 "score" (qsac_score_mfma_kernel or
  * qsac_score_valu_kernel), 2 "select" (qsac_select_small_kernel for N <= 131072, else
  * qsac_refine_kernel<1>, <2>, qsac_mark_kernel, qsac_diff_kernel), 3 "fill" (qsac_fill_kernel),
- * 4 "attn" (qsac_attn_kernel).  qsac_get_stage_ms() waits for the last profiled step and writes
+ * 4 "attn" (qsac_attn_kernel, qsac_combine_kernel).  qsac_get_stage_ms() waits for the last profiled step and writes
  * the summed duration of each stage in milliseconds to ms_sum[qsac_num_stages()] and the number
  * of steps summed to *n_steps.  A duration is the time between the events recorded on
  * stream_main before the stage's first kernel and before the next stage's.  qsac_stage_name(i)

@@ -79,7 +79,6 @@ void make_layout(const qsac_config* c, qsac_ws_layout* L) {
   L->stats = take(8 * 8);
   L->importance = take((size_t)c->n_q_heads * 8);
   L->sel_r = take(P * 4);
-  L->ticket = take(P * 4);
   L->total = off;
   L->n_pad = (int64_t)n_pad;
   L->words = (int32_t)words;
@@ -123,7 +122,6 @@ int clear_state(qsac_ctx* c) {
   qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.valid), (size_t)c->P);
   qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.stats), (size_t)16);
   qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.miss_count), (size_t)c->P);
-  qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.ticket), (size_t)c->P);
   HIP_TRY(hipGetLastError());
   c->k_bound = 0;
   c->steps = 0;
@@ -169,11 +167,11 @@ void launch_score(const qsac_ctx* c, const qsac_step_args* a, u32* keys, u32* hi
 }
 
 template <int DT, int G>
-void launch_attn(const qsac_ctx* c, const qsac_step_args* a, dim3 grid, float* part_ml, float* part_acc, int* ticket,
-                 int rows, int n_splits, int which) {
+void launch_attn(const qsac_ctx* c, const qsac_step_args* a, dim3 grid, float* part_ml, float* part_acc, int rows,
+                 int n_splits, int which) {
   qsac_attn_kernel<DT, G><<<grid, 256, 0, c->s_main>>>(
       static_cast<const uint16_t*>(a->q), static_cast<const v4u*>(a->K_slots), static_cast<const v4u*>(a->V_slots),
-      a->reuse_flags, part_ml, part_acc, ticket, a->out, c->cfg.n_q_heads, c->cfg.n_kv_heads, a->k, c->cfg.k_max,
+      a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads, c->cfg.n_kv_heads, a->k, c->cfg.k_max,
       rows, n_splits, c->L.max_splits, which);
 }
 
@@ -363,9 +361,20 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   // 3. select the k best, diff against the cache slots
   mark(2);
   if (c->small) {
-    qsac_select_small_kernel<<<P, kDiffThreads, 0, sm>>>(a->reuse_flags, keys, valid, a->slot_idx, set_sorted,
-                                                        a->topk_idx, a->hit_mask, miss_count, miss_slot, miss_tok,
-                                                        stats, N, L.n_pad, k, k_max);
+    // key vectors per thread that keep the pair's keys in registers (0: re-read them from L2)
+    const int64_t nvec = (N + 3) / 4;
+    const int bm_words = (int)((N + 63) / 64 * 2);
+    const size_t lds = (size_t)bm_words * 3 * sizeof(u32);
+#define QSAC_SELECT(VPT)                                                                                          \
+  qsac_select_small_kernel<VPT><<<P, kDiffThreads, lds, sm>>>(a->reuse_flags, keys, valid, a->slot_idx, set_sorted, \
+                                                             a->topk_idx, a->hit_mask, miss_count, miss_slot,      \
+                                                             miss_tok, stats, N, L.n_pad, k, k_max, bm_words)
+    if (nvec <= 2 * kDiffThreads) QSAC_SELECT(2);
+    else if (nvec <= 4 * kDiffThreads) QSAC_SELECT(4);
+    else if (nvec <= 8 * kDiffThreads) QSAC_SELECT(8);
+    else if (nvec <= 16 * kDiffThreads) QSAC_SELECT(16);
+    else QSAC_SELECT(0);
+#undef QSAC_SELECT
   } else {
     dim3 sel_grid((unsigned)(L.n_pad / kSelChunk), (unsigned)P);
     qsac_refine_kernel<1><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
@@ -381,14 +390,18 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   const int n_splits = (k + rows - 1) / rows;
   dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
   dim3 attn_grid((unsigned)n_splits, (unsigned)P);
-  int* ticket = reinterpret_cast<int*>(ws + L.ticket);
   auto fill_on = [&](hipStream_t s) {
     qsac_fill_kernel<<<fill_grid, 256, 0, s>>>(miss_count, miss_slot, miss_tok, static_cast<const v4u*>(a->K_src),
                                                static_cast<const v4u*>(a->V_src), static_cast<v4u*>(a->K_slots),
                                                static_cast<v4u*>(a->V_slots), N, k_max);
   };
   auto attend = [&](int which) {
-    QSAC_DISPATCH(launch_attn, c, a, attn_grid, part_ml, part_acc, ticket, rows, n_splits, which);
+    QSAC_DISPATCH(launch_attn, c, a, attn_grid, part_ml, part_acc, rows, n_splits, which);
+  };
+  auto combine = [&]() {
+    if (n_splits > 1)
+      qsac_combine_kernel<<<P * G, 128, 0, sm>>>(part_ml, part_acc, a->reuse_flags, a->out, Hq, Hkv, G, n_splits,
+                                                 L.max_splits, 0);
   };
   if (c->overlap) {
     // the fill runs on the side stream while the pairs that reused their cache are attended to
@@ -399,11 +412,13 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     attend(1);
     HIP_TRY(hipStreamWaitEvent(sm, c->ev_fill, 0));
     attend(2);
+    combine();
   } else {
     mark(3);
     fill_on(sm);
     mark(4);
     attend(0);
+    combine();
     mark(5);
     c->prof_pending = c->profile;
   }

@@ -13,8 +13,8 @@
 //            scoring kernel and the levels run as grid-wide kernels (refine1, refine2, mark,
 //            diff) so that a few pairs with very long contexts still fill the chip.
 //   fill     copies the missing K / V rows from the fill sources into the slots
-//   attn     softmax(q K_c^T / sqrt(d)) V_c over the slots (Section 2.1), split over slots;
-//            the last workgroup of a pair to finish merges the splits
+//   attn     softmax(q K_c^T / sqrt(d)) V_c over the slots (Section 2.1), split over slots
+//   combine  merges the splits
 //
 // Pairs whose gate reused the cache leave every miss-path kernel at once.
 #pragma once
@@ -633,27 +633,54 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
                             stats, s_wave);
 }
 
+// OR over aligned groups of 8 lanes (DPP: xor 1, xor 2, then mirror within each half row).
+__device__ __forceinline__ u32 or8(u32 v) {
+  v |= (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);
+  v |= (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, true);
+  v |= (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, true);
+  return v;
+}
+
 // Small-N path (N <= kSmallMaxN): one workgroup of 1024 threads per missing pair selects and
-// diffs in one go.  The pair's keys (4N bytes, just written by the scoring kernel) are read
-// four times from L2: three histogram passes (11 + 11 + 10 bits) that pin the k-th largest key
-// T exactly, one pass that ballots "key > T" and "key == T" into LDS bitmaps.
+// diffs in one go.  Three histogram passes (11 + 11 + 10 bits) pin the k-th largest key T
+// exactly; a fourth pass turns "key > T" and "key == T" into LDS bitmaps.  With VPT > 0 thread t
+// keeps key vectors t, t + 1024, ... (VPT of them, 4 keys each) in registers, so the keys are
+// read from memory once; VPT = 0 re-reads them (from L2) on every pass.  Dynamic LDS: three
+// bitmaps of bm_words words.
+template <int VPT>
 __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
     const uint8_t* __restrict__ reuse_flags, const u32* __restrict__ keys, u32* __restrict__ valid,
     int* __restrict__ slot_idx, int* __restrict__ set_sorted, int* __restrict__ topk_idx,
     uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count, int* __restrict__ miss_slot,
-    int* __restrict__ miss_tok, u64* __restrict__ stats, int64_t N, int64_t n_pad, int k, int k_max) {
+    int* __restrict__ miss_tok, u64* __restrict__ stats, int64_t N, int64_t n_pad, int k, int k_max,
+    int bm_words) {
   const int p = blockIdx.x;
   if (reuse_flags[p]) return;
   constexpr int NT = kDiffThreads;
+  constexpr int NV = VPT > 0 ? VPT : 1;
+  extern __shared__ u32 s_dyn[];
   __shared__ u32 s_hist[kBins];
-  __shared__ u32 s_new[kSmallMaxN / 32], s_eq[kSmallMaxN / 32], s_old[kSmallMaxN / 32];
   __shared__ int s_wave[17];
   __shared__ int s_res[2];
-  const int tid = threadIdx.x, lane = tid & 63;
+  u32* s_new = s_dyn;
+  u32* s_eq = s_dyn + bm_words;
+  u32* s_old = s_dyn + 2 * bm_words;
+  const int tid = threadIdx.x;
   const u32* kp = keys + (size_t)p * n_pad;
   const v4u* kp4 = reinterpret_cast<const v4u*>(kp);
   const int n = (int)N;
   const int nvec = (n + 3) >> 2;  // n_pad is a multiple of 8192, so whole vectors can be read
+  const int words = (n + 31) >> 5;
+
+  v4u kreg[NV];
+  if (VPT > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int v = tid + i * NT;
+      kreg[i] = v < nvec ? kp4[v] : v4u{0, 0, 0, 0};
+    }
+  }
+  for (int i = tid; i < bm_words; i += NT) s_old[i] = 0;
 
   int need = k, above;
   u32 prefix = 0;
@@ -665,8 +692,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
     const u32 mask = level == 2 ? 0x3ffu : 0x7ffu;
     for (int i = tid; i < kBins; i += NT) s_hist[i] = 0;
     __syncthreads();
-    for (int v = tid; v < nvec; v += NT) {
-      const v4u kk = kp4[v];
+    auto count = [&](const v4u kk, const int v) {
       const int e = v * 4;
       const u32 ks[4] = {kk.x, kk.y, kk.z, kk.w};
 #pragma unroll
@@ -674,6 +700,12 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
         const bool match = level == 0 || (ks[i] >> shift) == prefix;
         if (e + i < n && match) atomicAdd(&s_hist[(ks[i] >> sub) & mask], 1u);
       }
+    };
+    if (VPT > 0) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) count(kreg[i], tid + i * NT);
+    } else {
+      for (int v = tid; v < nvec; v += NT) count(kp4[v], v);
     }
     __syncthreads();
     const int nb = level == 2 ? 1024 : kBins;
@@ -681,24 +713,34 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
     need -= above;
     prefix = level == 0 ? b : (prefix << (level == 1 ? 11 : 10)) | b;
   }
-  const u32 T = prefix;   // the k-th largest key; `need` of the keys equal to it belong to the set
-  const int words = (n + 31) >> 5;
-  const int n64 = (n + 63) & ~63;
-  for (int base = (tid >> 6) * 64; base < n64; base += NT) {
-    const int e = base + lane;
-    const bool in = e < n;
-    const u32 key = in ? kp[e] : 0u;
-    const u64 mg = __ballot(in && key > T);
-    const u64 me = __ballot(in && key == T);
-    const int w = e >> 5;
-    if (lane == 0) {
-      s_new[w] = (u32)mg;
-      s_eq[w] = (u32)me;
-      s_old[w] = 0;
-    } else if (lane == 32) {
-      s_new[w] = (u32)(mg >> 32);
-      s_eq[w] = (u32)(me >> 32);
-      s_old[w] = 0;
+  const u32 T = prefix;  // the k-th largest key; `need` of the keys equal to it belong to the set
+  // bitmaps: a key vector is a nibble; 8 neighbouring lanes hold the 8 nibbles of one word
+  auto nibbles = [&](const v4u kk, const int v) {
+    const int e = v * 4;
+    const u32 ks[4] = {kk.x, kk.y, kk.z, kk.w};
+    u32 g = 0, q = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bool in = e + i < n;
+      g |= (u32)(in && ks[i] > T) << i;
+      q |= (u32)(in && ks[i] == T) << i;
+    }
+    const int sh = (v & 7) * 4;
+    g = or8(g << sh);
+    q = or8(q << sh);
+    if ((v & 7) == 0 && (v >> 3) < words) {
+      s_new[v >> 3] = g;
+      s_eq[v >> 3] = q;
+    }
+  };
+  const int nvec8 = (nvec + 7) & ~7;  // whole groups of 8 lanes stay together for or8
+  if (VPT > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) nibbles(kreg[i], tid + i * NT);
+  } else {
+    for (int v0 = 0; v0 < nvec8; v0 += NT) {  // uniform trip count: every lane takes part in or8
+      const int v = v0 + tid;
+      nibbles(v < nvec ? kp4[v] : v4u{0, 0, 0, 0}, v);
     }
   }
   __syncthreads();
@@ -764,14 +806,13 @@ __device__ __forceinline__ bool pair_selected(int which, const uint8_t* reuse_fl
 // its lanes form the G dot products with v_dot2, sum them over the row, and every lane keeps
 // its own online-softmax state (running max, sum, 8 output channels per head) for the slots of
 // its row group.  Tiles of 16 slots per wave share one rescale.  Row groups, then waves, are
-// merged at the end; the split's (max, sum, unnormalised output) goes to the workspace and the
-// last workgroup of the pair to finish merges the splits and writes the output.
+// merged at the end; the split's (max, sum, unnormalised output) goes to the workspace for
+// qsac_combine_kernel, or, when the pair has a single split, the output is written directly.
 template <int DT, int G>
 __global__ __launch_bounds__(256) void qsac_attn_kernel(
     const uint16_t* __restrict__ q, const v4u* __restrict__ K_slots, const v4u* __restrict__ V_slots,
     const uint8_t* __restrict__ reuse_flags, float* __restrict__ part_ml, float* __restrict__ part_acc,
-    int* __restrict__ ticket, float* __restrict__ out, int Hq, int Hkv, int k, int k_max, int rows, int n_splits,
-    int max_splits, int which) {
+    float* __restrict__ out, int Hq, int Hkv, int k, int k_max, int rows, int n_splits, int max_splits, int which) {
   const int p = blockIdx.y, split = blockIdx.x;
   if (!pair_selected(which, reuse_flags, p)) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -870,7 +911,6 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
   // merge the four waves through LDS
   __shared__ float s_ml[4][G][2];
   __shared__ float s_acc[4][G][kD];
-  __shared__ int s_last;
   if (r == 0) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -909,34 +949,36 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
       }
     }
   }
-  if (n_splits == 1) return;
-  // The last workgroup of the pair to get here merges the splits (in split order, so the result
-  // does not depend on which one that is).
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const int t = atomicAdd(&ticket[p], 1);
-    s_last = (t == n_splits - 1);
+}
+
+// One workgroup of 128 threads per query head: merges the attention splits and normalises.
+// (Merging inside the attention kernel, by the last workgroup of a pair to finish, needs a
+// device-scope release/acquire per workgroup, which on this multi-die part writes back and
+// invalidates L2 and cost ten times what this launch does.)
+__global__ __launch_bounds__(128) void qsac_combine_kernel(const float* __restrict__ part_ml,
+                                                           const float* __restrict__ part_acc,
+                                                           const uint8_t* __restrict__ reuse_flags,
+                                                           float* __restrict__ out, int Hq, int Hkv, int G,
+                                                           int n_splits, int max_splits, int which) {
+  const int pg = blockIdx.x;  // p * G + g
+  const int p = pg / G, g = pg % G;
+  if (!pair_selected(which, reuse_flags, p)) return;
+  const int d = threadIdx.x;
+  const float kNegInf = -__builtin_inff();
+  const float* ml = part_ml + (size_t)pg * max_splits * 2;
+  const float* pa = part_acc + (size_t)pg * max_splits * kD;
+  float M = kNegInf;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml[s * 2]);
+  float L = 0.f, A = 0.f;
+#pragma unroll 8
+  for (int s = 0; s < n_splits; ++s) {
+    const float ms = ml[s * 2];
+    const float wt = (ms == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+    L += ml[s * 2 + 1] * wt;
+    A += pa[(size_t)s * kD + d] * wt;
   }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  for (int i = threadIdx.x; i < G * kD; i += 256) {
-    const int g = i >> 7, d = i & 127;
-    const float* ml = part_ml + ((size_t)p * G + g) * max_splits * 2;
-    const float* pa = part_acc + ((size_t)p * G + g) * max_splits * kD;
-    float M = kNegInf;
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml[s * 2]);
-    float L = 0.f, A = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-      const float ms = ml[s * 2];
-      const float wt = (ms == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
-      L += ml[s * 2 + 1] * wt;
-      A += pa[(size_t)s * kD + d] * wt;
-    }
-    out_p[i] = A / L;
-  }
-  if (threadIdx.x == 0) ticket[p] = 0;  // ready for the next launch
+  const int b = p / Hkv, h = p % Hkv;
+  out[((size_t)b * Hq + (size_t)h * G + g) * kD + d] = A / L;
 }
 
 // Clears `n` 32-bit words (used instead of a memset node so that the step can be captured in a graph).
