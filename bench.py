@@ -93,10 +93,8 @@ def main():
     torch.cuda.synchronize()
 
     def session(flags):
-        # the fill runs on a side stream only where it crosses PCIe; from HBM it is too short to be worth two
-        # attention launches
         return Q.Session(w.B, w.Hq, w.Hkv, w.N, w.k, w.dtype, K_dev, K_src, V_src, flags=flags | a.flags,
-                         side_stream=(w.host_k or w.host_v))
+                         side_stream=bool(a.flags & Q.QSAC_FLAG_FILL_KERNEL))
 
     # ---- timed run: K steps after W warmup steps, overlapped fill, no events inside
     sess = session(0)
@@ -125,7 +123,8 @@ def main():
                    "n_ctx": w.N, "k": w.k, "tau": tau, "rho": list(w.rho_range) if w.rho_range else w.rho,
                    "K_fill_source": "pinned host" if w.host_k else "HBM",
                    "V_fill_source": "pinned host" if w.host_v else "HBM",
-                   "scoring": "alu" if (a.flags & Q.QSAC_FLAG_SCORE_VALU) else "mfma"},
+                   "scoring": "alu" if (a.flags & Q.QSAC_FLAG_SCORE_VALU) else "mfma",
+                   "fill": "own kernel on a side stream" if (a.flags & Q.QSAC_FLAG_FILL_KERNEL) else "folded into attention loads"},
         "reuse_rate": reuse_rate, "slot_hit_rate": slot_hit_rate,
         "rows_filled_per_step": d["slot_misses"] / K_steps,
     }

@@ -63,9 +63,12 @@ enum {
 /* qsac_config.flags */
 enum {
   QSAC_FLAG_DRY_RUN = 1,     /* validate only: the ctx never touches a device (for hosts without a GPU) */
-  QSAC_FLAG_SERIAL = 2,      /* run the miss fill on stream_main even when stream_side is given           */
+  QSAC_FLAG_SERIAL = 2,      /* with QSAC_FLAG_FILL_KERNEL: fill on stream_main even when stream_side is given */
   QSAC_FLAG_SCORE_VALU = 4,  /* score with packed dot-product ALU ops instead of the MFMA tile           */
-  QSAC_FLAG_PROFILE = 8      /* bracket every stage with timing events (single stream; see qsac_get_stage_ms) */
+  QSAC_FLAG_PROFILE = 8,     /* bracket every stage with timing events (single stream; see qsac_get_stage_ms) */
+  QSAC_FLAG_FILL_KERNEL = 16 /* fill the missing rows with a kernel of its own (on stream_side if given, overlapped
+                                with the attention of the heads that reused) instead of folding the fetch into the
+                                attention kernel's row loads                                              */
 };
 
 typedef struct qsac_ctx qsac_ctx;
@@ -77,7 +80,7 @@ typedef struct {
   int32_t dtype;                /* QSAC_F16 | QSAC_BF16: type of q, K, V, prev_q and the slots           */
   const float *q_head_importance; /* HOST, [n_q_heads] weights s_j of Eq. (2), all > 0; NULL = all 1     */
   void *stream_main;            /* hipStream_t (NULL = default stream); borrowed                          */
-  void *stream_side;            /* hipStream_t for the miss fill, or NULL to fill on stream_main; borrowed */
+  void *stream_side;            /* hipStream_t for the fill kernel (QSAC_FLAG_FILL_KERNEL), or NULL; borrowed */
   void *workspace;              /* DEVICE, 256-byte aligned, >= qsac_workspace_bytes(); caller-owned       */
   size_t workspace_bytes;
   int32_t flags;
@@ -100,6 +103,7 @@ typedef struct {
   size_t stats;      /* u64 [8]              cumulative counters                                          */
   size_t importance; /* f64 [n_q_heads]      Eq. (2) weights                                              */
   size_t sel_r;      /* i32 [P]              keys equal to the k-th key that belong to the set (last miss)        */
+  size_t fetch_tok;  /* i32 [P][k_max]       per slot: token whose rows the slot still has to receive, or -1      */
   size_t total;      /* bytes needed                                                                      */
   int64_t n_pad;     /* N rounded up to the select chunk                                                  */
   int32_t words;     /* 32-bit words per bitmap                                                           */

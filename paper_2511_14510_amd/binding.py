@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "csrc", "libqsac.so")
 QSAC_F16, QSAC_BF16 = 0, 1
 QSAC_OK, QSAC_EINVAL, QSAC_ENULL, QSAC_ERANGE = 0, -1, -2, -3
 QSAC_EWORKSPACE, QSAC_EHIP, QSAC_ESTATE, QSAC_EALIGN = -4, -5, -6, -7
-QSAC_FLAG_DRY_RUN, QSAC_FLAG_SERIAL, QSAC_FLAG_SCORE_VALU, QSAC_FLAG_PROFILE = 1, 2, 4, 8
+QSAC_FLAG_DRY_RUN, QSAC_FLAG_SERIAL, QSAC_FLAG_SCORE_VALU, QSAC_FLAG_PROFILE, QSAC_FLAG_FILL_KERNEL = 1, 2, 4, 8, 16
 QSAC_MAX_GROUP, QSAC_MAX_KV_HEADS, QSAC_HEAD_DIM = 8, 64, 128
 
 EXPORTS = ("qsac_workspace_bytes", "qsac_workspace_layout", "qsac_init", "qsac_reset", "qsac_step",
@@ -36,7 +36,7 @@ class qsac_config(C.Structure):
 class qsac_ws_layout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
                 ("valid", "set_sorted", "keys", "hist", "bm_new", "bm_eq", "bm_old", "miss_count", "miss_slot",
-                 "miss_tok", "part_ml", "part_acc", "stats", "importance", "sel_r", "total")] + \
+                 "miss_tok", "part_ml", "part_acc", "stats", "importance", "sel_r", "fetch_tok", "total")] + \
                [("n_pad", C.c_int64), ("words", C.c_int32), ("max_splits", C.c_int32)]
 
 

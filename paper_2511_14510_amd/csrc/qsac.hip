@@ -35,20 +35,22 @@ int check_config(const qsac_config* c) {
   if (c->n_ctx < 1 || c->n_ctx > (int64_t(1) << 24)) return QSAC_ERANGE;
   if (c->k_max < 1 || c->k_max > c->n_ctx) return QSAC_ERANGE;
   if ((int64_t)c->batch * c->n_kv_heads > 65535) return QSAC_ERANGE;  // grid.y
-  if (c->flags & ~(QSAC_FLAG_DRY_RUN | QSAC_FLAG_SERIAL | QSAC_FLAG_SCORE_VALU | QSAC_FLAG_PROFILE)) return QSAC_EINVAL;
+  if (c->flags & ~(QSAC_FLAG_DRY_RUN | QSAC_FLAG_SERIAL | QSAC_FLAG_SCORE_VALU | QSAC_FLAG_PROFILE | QSAC_FLAG_FILL_KERNEL)) return QSAC_EINVAL;
   if (c->q_head_importance)
     for (int i = 0; i < c->n_q_heads; ++i)
       if (!(c->q_head_importance[i] > 0.f) || !std::isfinite(c->q_head_importance[i])) return QSAC_EINVAL;
   return QSAC_OK;
 }
 
-// Attention split: rows of slots per workgroup for k slots in use.  Aims at >= 1024 workgroups
-// (four per compute unit) while keeping at least 64 rows, i.e. one 16-row tile per wave, each.
+// Attention split: rows of slots per workgroup for k slots in use.  The kernel keeps two waves per
+// SIMD resident, i.e. two workgroups per compute unit, so about 512 workgroups fill the chip in one
+// round (measured: 512 beats 256, 768, 1024 and 2048 at 64 pairs x 2048 slots); at least 64 rows,
+// one 16-slot tile per wave, each.
 int attn_rows(int P, int k) {
-  int64_t rows = ((int64_t)P * k + 1023) / 1024;
+  int64_t rows = ((int64_t)P * k + 511) / 512;
   rows = (rows + 63) / 64 * 64;
   if (rows < 64) rows = 64;
-  if (rows > 512) rows = 512;
+  if (rows > 1024) rows = 1024;
   return (int)rows;
 }
 
@@ -79,6 +81,7 @@ void make_layout(const qsac_config* c, qsac_ws_layout* L) {
   L->stats = take(8 * 8);
   L->importance = take((size_t)c->n_q_heads * 8);
   L->sel_r = take(P * 4);
+  L->fetch_tok = take(P * c->k_max * 4);
   L->total = off;
   L->n_pad = (int64_t)n_pad;
   L->words = (int32_t)words;
@@ -96,7 +99,7 @@ struct qsac_ctx {
   uint64_t steps;
   hipStream_t s_main, s_side;
   hipEvent_t ev_sel, ev_fill;
-  bool dry, overlap, profile, small;
+  bool dry, overlap, profile, small, fill_kernel;
   hipEvent_t prof[kStages + 1];
   double stage_ms[kStages];
   uint64_t stage_calls;
@@ -167,12 +170,21 @@ void launch_score(const qsac_ctx* c, const qsac_step_args* a, u32* keys, u32* hi
 }
 
 template <int DT, int G>
-void launch_attn(const qsac_ctx* c, const qsac_step_args* a, dim3 grid, float* part_ml, float* part_acc, int rows,
-                 int n_splits, int which) {
-  qsac_attn_kernel<DT, G><<<grid, 256, 0, c->s_main>>>(
-      static_cast<const uint16_t*>(a->q), static_cast<const v4u*>(a->K_slots), static_cast<const v4u*>(a->V_slots),
-      a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads, c->cfg.n_kv_heads, a->k, c->cfg.k_max,
-      rows, n_splits, c->L.max_splits, which);
+void launch_attn(const qsac_ctx* c, const qsac_step_args* a, dim3 grid, const int* fetch_tok, const int* miss_count,
+                 float* part_ml, float* part_acc, int rows, int n_splits, int which) {
+  auto q = static_cast<const uint16_t*>(a->q);
+  auto Ks = static_cast<v4u*>(a->K_slots);
+  auto Vs = static_cast<v4u*>(a->V_slots);
+  auto Kf = static_cast<const v4u*>(a->K_src);
+  auto Vf = static_cast<const v4u*>(a->V_src);
+  if (c->fill_kernel)
+    qsac_attn_kernel<DT, G, false><<<grid, 256, 0, c->s_main>>>(
+        q, Ks, Vs, Kf, Vf, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads,
+        c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits, which);
+  else
+    qsac_attn_kernel<DT, G, true><<<grid, 256, 0, c->s_main>>>(
+        q, Ks, Vs, Kf, Vf, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads,
+        c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits, which);
 }
 
 // Dispatch on (dtype, G) to the instantiated kernels.
@@ -240,7 +252,9 @@ int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
   c->small = cfg->n_ctx <= kSmallMaxN;
   c->s_main = static_cast<hipStream_t>(cfg->stream_main);
   c->s_side = static_cast<hipStream_t>(cfg->stream_side);
-  c->overlap = cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main && !(cfg->flags & QSAC_FLAG_SERIAL);
+  c->fill_kernel = (cfg->flags & QSAC_FLAG_FILL_KERNEL) != 0;
+  c->overlap = c->fill_kernel && cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main &&
+               !(cfg->flags & QSAC_FLAG_SERIAL);
   c->profile = (cfg->flags & QSAC_FLAG_PROFILE) != 0;
   if (c->profile) c->overlap = false;  // stage times are taken on one stream
   c->k_bound = 0;
@@ -328,6 +342,7 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   u64* stats = reinterpret_cast<u64*>(ws + L.stats);
   const double* importance = reinterpret_cast<const double*>(ws + L.importance);
   int* sel_r = reinterpret_cast<int*>(ws + L.sel_r);
+  int* fetch_tok = reinterpret_cast<int*>(ws + L.fetch_tok);
 
   const int P = c->P, G = c->G, k = a->k, k_max = c->cfg.k_max;
   const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
@@ -368,7 +383,7 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
 #define QSAC_SELECT(VPT)                                                                                          \
   qsac_select_small_kernel<VPT><<<P, kDiffThreads, lds, sm>>>(a->reuse_flags, keys, valid, a->slot_idx, set_sorted, \
                                                              a->topk_idx, a->hit_mask, miss_count, miss_slot,      \
-                                                             miss_tok, stats, N, L.n_pad, k, k_max, bm_words)
+                                                             miss_tok, fetch_tok, stats, N, L.n_pad, k, k_max, bm_words)
     if (nvec <= 2 * kDiffThreads) QSAC_SELECT(2);
     else if (nvec <= 4 * kDiffThreads) QSAC_SELECT(4);
     else if (nvec <= 8 * kDiffThreads) QSAC_SELECT(8);
@@ -383,9 +398,9 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
                                               L.words, k);
     qsac_diff_kernel<<<P, kDiffThreads, 0, sm>>>(a->reuse_flags, valid, bm_new, bm_eq, bm_old, sel_r, a->slot_idx,
                                                 set_sorted, a->topk_idx, a->hit_mask, miss_count, miss_slot,
-                                                miss_tok, stats, L.words, k, k_max);
+                                                miss_tok, fetch_tok, stats, L.words, k, k_max);
   }
-  // 4. fill the missing rows; 5. attention
+  // 4. fill the missing rows (own kernel, or folded into the attention kernel's loads); 5. attention
   const int rows = attn_rows(P, k);
   const int n_splits = (k + rows - 1) / rows;
   dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
@@ -396,7 +411,7 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
                                                static_cast<v4u*>(a->V_slots), N, k_max);
   };
   auto attend = [&](int which) {
-    QSAC_DISPATCH(launch_attn, c, a, attn_grid, part_ml, part_acc, rows, n_splits, which);
+    QSAC_DISPATCH(launch_attn, c, a, attn_grid, fetch_tok, miss_count, part_ml, part_acc, rows, n_splits, which);
   };
   auto combine = [&]() {
     if (n_splits > 1)
@@ -415,7 +430,7 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     combine();
   } else {
     mark(3);
-    fill_on(sm);
+    if (c->fill_kernel) fill_on(sm);
     mark(4);
     attend(0);
     combine();

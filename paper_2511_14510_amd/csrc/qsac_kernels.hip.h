@@ -12,7 +12,9 @@
 //            of it with its bitmaps in LDS.  Beyond: the first histogram is fused into the
 //            scoring kernel and the levels run as grid-wide kernels (refine1, refine2, mark,
 //            diff) so that a few pairs with very long contexts still fill the chip.
-//   fill     copies the missing K / V rows from the fill sources into the slots
+//   fill     copies the missing K / V rows from the fill sources into the slots; by default this
+//            is folded into the attention kernel's row loads ("fill on read"), the separate
+//            kernel (optionally on a side stream) is kept as the alternative
 //   attn     softmax(q K_c^T / sqrt(d)) V_c over the slots (Section 2.1), split over slots
 //   combine  merges the splits
 //
@@ -515,14 +517,16 @@ __global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restric
 //  B. bitmap of the tokens cached before the step (from slot_idx);
 //  C. ascending index list, hit mask, ascending list of tokens to fetch;
 //  D. ascending list of slots whose token left the set;
-//  E. the i-th such slot takes the i-th token to fetch.
+//  E. the i-th such slot takes the i-th token to fetch (slot table and fetch_tok).
 template <int NT>
 __device__ __forceinline__ void diff_phases(u32* nw, const u32* eq, u32* old, bool was_valid, int r, int words,
                                             int k, int* __restrict__ sl, int* __restrict__ ss,
                                             int* __restrict__ tk, uint8_t* __restrict__ hm, int* __restrict__ ms,
-                                            int* __restrict__ mt, int* __restrict__ miss_count_p,
-                                            u32* __restrict__ valid_p, u64* __restrict__ stats, int* s_wave) {
+                                            int* __restrict__ mt, int* __restrict__ ft,
+                                            int* __restrict__ miss_count_p, u32* __restrict__ valid_p,
+                                            u64* __restrict__ stats, int* s_wave) {
   const int tid = threadIdx.x;
+  for (int j = tid; j < k; j += NT) ft[j] = -1;  // slots that keep their row; E names the others
   const int wpt = (words + NT - 1) / NT;
   const int w0 = min(tid * wpt, words), w1 = min(w0 + wpt, words);
   int total;
@@ -607,7 +611,11 @@ __device__ __forceinline__ void diff_phases(u32* nw, const u32* eq, u32* old, bo
   }
   __syncthreads();
   // E
-  for (int i = tid; i < m; i += NT) sl[ms[i]] = mt[i];
+  for (int i = tid; i < m; i += NT) {
+    const int slot = ms[i], tok = mt[i];
+    sl[slot] = tok;
+    ft[slot] = tok;
+  }
   if (tid == 0) {
     *miss_count_p = m;
     *valid_p = 1;
@@ -622,15 +630,16 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
     const u32* __restrict__ bm_eq, u32* __restrict__ bm_old, const int* __restrict__ sel_r,
     int* __restrict__ slot_idx, int* __restrict__ set_sorted, int* __restrict__ topk_idx,
     uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count, int* __restrict__ miss_slot,
-    int* __restrict__ miss_tok, u64* __restrict__ stats, int words, int k, int k_max) {
+    int* __restrict__ miss_tok, int* __restrict__ fetch_tok, u64* __restrict__ stats, int words, int k,
+    int k_max) {
   const int p = blockIdx.x;
   if (reuse_flags[p]) return;
   __shared__ int s_wave[17];
   diff_phases<kDiffThreads>(bm_new + (size_t)p * words, bm_eq + (size_t)p * words, bm_old + (size_t)p * words,
                             valid[p] != 0, sel_r[p], words, k, slot_idx + (size_t)p * k_max,
                             set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
-                            miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max, miss_count + p, valid + p,
-                            stats, s_wave);
+                            miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max,
+                            fetch_tok + (size_t)p * k_max, miss_count + p, valid + p, stats, s_wave);
 }
 
 // OR over aligned groups of 8 lanes (DPP: xor 1, xor 2, then mirror within each half row).
@@ -652,8 +661,8 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
     const uint8_t* __restrict__ reuse_flags, const u32* __restrict__ keys, u32* __restrict__ valid,
     int* __restrict__ slot_idx, int* __restrict__ set_sorted, int* __restrict__ topk_idx,
     uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count, int* __restrict__ miss_slot,
-    int* __restrict__ miss_tok, u64* __restrict__ stats, int64_t N, int64_t n_pad, int k, int k_max,
-    int bm_words) {
+    int* __restrict__ miss_tok, int* __restrict__ fetch_tok, u64* __restrict__ stats, int64_t N, int64_t n_pad,
+    int k, int k_max, int bm_words) {
   const int p = blockIdx.x;
   if (reuse_flags[p]) return;
   constexpr int NT = kDiffThreads;
@@ -746,8 +755,8 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
   __syncthreads();
   diff_phases<NT>(s_new, s_eq, s_old, valid[p] != 0, need, words, k, slot_idx + (size_t)p * k_max,
                   set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
-                  miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max, miss_count + p, valid + p, stats,
-                  s_wave);
+                  miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max, fetch_tok + (size_t)p * k_max,
+                  miss_count + p, valid + p, stats, s_wave);
 }
 
 // ---------------------------------------------------------------- fill
@@ -802,125 +811,230 @@ __device__ __forceinline__ bool pair_selected(int which, const uint8_t* reuse_fl
 }
 
 // Workgroup (split, pair): slots [split*rows, split*rows + rows) of the pair, all G query heads.
-// A 16-lane DPP row takes one slot per load (16 bytes of the K row and of the V row per lane);
-// its lanes form the G dot products with v_dot2, sum them over the row, and every lane keeps
-// its own online-softmax state (running max, sum, 8 output channels per head) for the slots of
-// its row group.  Tiles of 16 slots per wave share one rescale.  Row groups, then waves, are
-// merged at the end; the split's (max, sum, unnormalised output) goes to the workspace for
-// qsac_combine_kernel, or, when the pair has a single split, the output is written directly.
-template <int DT, int G>
+// Wave w takes the 16-slot tiles w, w+4, ... of the range.  Per tile:
+//   - K and V rows arrive by fully coalesced loads (lane l: row 4j + l/16 of the tile, 16-byte
+//     piece l%16, j = 0..3); the next tile's loads are in flight while this one is consumed;
+//   - the K tile goes through a wave-private LDS tile into four v_mfma_f32_16x16x32 against the
+//     zero-padded query group (as in the scoring kernel): lane l then holds the logits of slot
+//     l%16 for queries 4*(l/16) .. +3;
+//   - those lanes do the online softmax for their queries (tile maximum by DPP over the 16
+//     slots, one exp per logit), and publish the 16 x G weights and the G rescale factors in
+//     LDS;
+//   - every lane folds its four V rows (8 channels each) into acc[g][8] with plain FMAs, reading
+//     its rows' weights back from LDS.
+// All lanes of a wave share the running maxima, so the four row groups add up without
+// rescaling; waves are merged through LDS.  The split's (max, sum, unnormalised output) goes to
+// the workspace for qsac_combine_kernel, or, when the pair has a single split, the output is
+// written directly.
+//
+// FETCH ("fill on read"): a slot whose entry in fetch_tok is a token (>= 0) has no row yet: its
+// K and V rows are read from the fill sources instead of the slot and written into the slot on
+// the way, so the miss fill costs no pass of its own.  Each slot belongs to exactly one lane
+// of one workgroup per 16-byte piece, so nothing else reads or writes it during the launch.
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_move<0xB1>(v));
+  v = fmaxf(v, dpp_move<0x4E>(v));
+  v = fmaxf(v, dpp_move<0x141>(v));
+  v = fmaxf(v, dpp_move<0x140>(v));
+  return v;
+}
+
+template <int DT, int G, bool FETCH>
 __global__ __launch_bounds__(256) void qsac_attn_kernel(
-    const uint16_t* __restrict__ q, const v4u* __restrict__ K_slots, const v4u* __restrict__ V_slots,
-    const uint8_t* __restrict__ reuse_flags, float* __restrict__ part_ml, float* __restrict__ part_acc,
-    float* __restrict__ out, int Hq, int Hkv, int k, int k_max, int rows, int n_splits, int max_splits, int which) {
+    const uint16_t* __restrict__ q, v4u* __restrict__ K_slots, v4u* __restrict__ V_slots,
+    const v4u* __restrict__ K_src, const v4u* __restrict__ V_src, const int* __restrict__ fetch_tok,
+    const int* __restrict__ miss_count, const uint8_t* __restrict__ reuse_flags, float* __restrict__ part_ml,
+    float* __restrict__ part_acc, float* __restrict__ out, int Hq, int Hkv, int64_t N, int k, int k_max, int rows,
+    int n_splits, int max_splits, int which) {
   const int p = blockIdx.y, split = blockIdx.x;
   if (!pair_selected(which, reuse_flags, p)) return;
+  constexpr int GP = G > 4 ? 8 : 4;  // queries padded to whole lane quarters
+  __shared__ __attribute__((aligned(16))) unsigned char s_tile[4][16 * kTilePitch];
+  __shared__ __attribute__((aligned(16))) float s_p[4][16][GP];
+  __shared__ __attribute__((aligned(16))) float s_alpha[4][GP];
+  __shared__ float s_ml[4][G][2];
+  __shared__ float s_acc[4][G][kD];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int c = lane & 15, r = lane >> 4;
+  const int m = lane & 15, quarter = lane >> 4;
   const int b = p / Hkv, h = p % Hkv;
   const v4u* qg = reinterpret_cast<const v4u*>(q + ((size_t)b * Hq + (size_t)h * G) * kD);
-  v4u qf[G];
+  v4u qa[4];
 #pragma unroll
-  for (int g = 0; g < G; ++g) qf[g] = qg[g * kRowU4 + c];
-  const v4u* Kp = K_slots + (size_t)p * k_max * kRowU4;
-  const v4u* Vp = V_slots + (size_t)p * k_max * kRowU4;
+  for (int j = 0; j < 4; ++j) qa[j] = (m < G) ? qg[m * kRowU4 + quarter * 4 + j] : v4u{0, 0, 0, 0};
+  v4u* Kp = K_slots + (size_t)p * k_max * kRowU4;
+  v4u* Vp = V_slots + (size_t)p * k_max * kRowU4;
+  const v4u* Ks = K_src + (size_t)p * (size_t)N * kRowU4;
+  const v4u* Vs = V_src + (size_t)p * (size_t)N * kRowU4;
+  const int* ft = fetch_tok + (size_t)p * k_max;
+  const bool fetch = FETCH && miss_count[p] > 0;  // uniform over the workgroup
 
   const float kScale = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
   const float kNegInf = -__builtin_inff();
-  float mx[G], sum[G], acc[G][8];
+  float mrun[4], lrun[4];  // queries 4*quarter + i: running maximum (log2 domain), this lane's share of the sum
+  float acc[G][8];         // channels 8m .. 8m+7 of every query, over the rows of this lane's row group
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    mx[g] = kNegInf;
-    sum[g] = 0.f;
+  for (int i = 0; i < 4; ++i) {
+    mrun[i] = kNegInf;
+    lrun[i] = 0.f;
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g)
 #pragma unroll
     for (int d = 0; d < 8; ++d) acc[g][d] = 0.f;
-  }
 
   const int s_begin = split * rows;
   const int s_end = min(s_begin + rows, k);
-  // wave w takes tiles w, w+4, ... of 16 slots; row group r takes slots 4r..4r+3 of the tile
-  for (int t0 = s_begin + wave * 16; t0 < s_end; t0 += 64) {
-    v4u kv[4], vv[4];
-    bool ok[4];
+
+  // tokens to fetch for this lane's four rows of the tile at t0 (-1: the row is in its slot).
+  // Rows past the end of the range repeat the last row, so that what is loaded is always real data.
+  auto load_tok = [&](int t0, int (&tok)[4]) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      int j = t0 + r * 4 + u;
-      ok[u] = j < s_end;
-      j = ok[u] ? j : s_end - 1;
-      kv[u] = Kp[(size_t)j * kRowU4 + c];
-      vv[u] = Vp[(size_t)j * kRowU4 + c];
+    for (int j = 0; j < 4; ++j) {
+      int row = t0 + 4 * j + quarter;
+      row = row < s_end ? row : s_end - 1;
+      tok[j] = fetch ? ft[row] : -1;
     }
-    float vf[4][8];
+  };
+  // issue the loads of this lane's four K (or V) rows of the tile at t0
+  auto load_tile = [&](int t0, const int (&tok)[4], v4u (&dst)[4], const v4u* slots, const v4u* src) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      vf[u][0] = lo16<DT>(vv[u].x); vf[u][1] = hi16<DT>(vv[u].x);
-      vf[u][2] = lo16<DT>(vv[u].y); vf[u][3] = hi16<DT>(vv[u].y);
-      vf[u][4] = lo16<DT>(vv[u].z); vf[u][5] = hi16<DT>(vv[u].z);
-      vf[u][6] = lo16<DT>(vv[u].w); vf[u][7] = hi16<DT>(vv[u].w);
+    for (int j = 0; j < 4; ++j) {
+      int row = t0 + 4 * j + quarter;
+      row = row < s_end ? row : s_end - 1;
+      const v4u* from = slots + (size_t)row * kRowU4;
+      if (FETCH && tok[j] >= 0) from = src + (size_t)tok[j] * kRowU4;
+      dst[j] = from[m];
     }
+  };
+  // fetched rows go into their slots
+  auto store_fetched = [&](int t0, const int (&tok)[4], const v4u (&val)[4], v4u* slots) {
+    if (FETCH) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float s[4];
-      float tmax = kNegInf;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        s[u] = row16_sum(dot8<DT>(qf[g], kv[u])) * kScale;
-        s[u] = ok[u] ? s[u] : kNegInf;
-        tmax = fmaxf(tmax, s[u]);
+      for (int j = 0; j < 4; ++j) {
+        const int row = t0 + 4 * j + quarter;
+        if (tok[j] >= 0 && row < s_end) slots[(size_t)row * kRowU4 + m] = val[j];
       }
-      const float mnew = fmaxf(mx[g], tmax);
-      if (mnew != kNegInf) {  // at least one real slot so far
-        const float alpha = (mx[g] == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mx[g] - mnew);
-        float pw[4];
+    }
+  };
+  // K tile -> LDS -> logits -> online softmax -> weights and rescale factors in LDS
+  auto stage_k = [&](const v4u (&kk)[4]) {
+    unsigned char* tile = s_tile[wave];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) pw[u] = ok[u] ? __builtin_amdgcn_exp2f(s[u] - mnew) : 0.f;
-        sum[g] = sum[g] * alpha + ((pw[0] + pw[1]) + (pw[2] + pw[3]));
+    for (int j = 0; j < 4; ++j) *reinterpret_cast<v4u*>(tile + (4 * j + quarter) * kTilePitch + m * 16) = kk[j];
+    __builtin_amdgcn_wave_barrier();
+  };
+  auto softmax_tile = [&](int t0) {
+    const unsigned char* tile = s_tile[wave];
+    f4_t sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int d = 0; d < 8; ++d) {
-          float a = acc[g][d] * alpha;
-          a = fmaf(pw[0], vf[0][d], a);
-          a = fmaf(pw[1], vf[1][d], a);
-          a = fmaf(pw[2], vf[2][d], a);
-          a = fmaf(pw[3], vf[3][d], a);
-          acc[g][d] = a;
-        }
-        mx[g] = mnew;
+    for (int j = 0; j < 4; ++j) {
+      const v4u kb = *reinterpret_cast<const v4u*>(tile + m * kTilePitch + (quarter * 4 + j) * 16);
+      sc = mfma16<DT>(qa[j], kb, sc);
+    }
+    // sc[i]: logit of query 4*quarter + i against slot t0 + m
+    const bool slot_ok = t0 + m < s_end;
+    f4_t pw, al;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float sv = slot_ok ? sc[i] * kScale : kNegInf;
+      const float mnew = fmaxf(mrun[i], row16_max(sv));  // finite: slot t0 is real
+      al[i] = (mrun[i] == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mrun[i] - mnew);
+      pw[i] = slot_ok ? __builtin_amdgcn_exp2f(sv - mnew) : 0.f;
+      lrun[i] = lrun[i] * al[i] + pw[i];
+      mrun[i] = mnew;
+    }
+    if (quarter * 4 < GP) {
+      *reinterpret_cast<f4_t*>(&s_p[wave][m][quarter * 4]) = pw;
+      if (m == 0) *reinterpret_cast<f4_t*>(&s_alpha[wave][quarter * 4]) = al;
+    }
+    __builtin_amdgcn_wave_barrier();
+  };
+  // acc <- acc * alpha + sum over this lane's four rows of weight * V row
+  auto fold_v = [&](const v4u (&vv)[4]) {
+    float a[GP];
+    *reinterpret_cast<f4_t*>(&a[0]) = *reinterpret_cast<const f4_t*>(&s_alpha[wave][0]);
+    if (GP > 4) *reinterpret_cast<f4_t*>(&a[4]) = *reinterpret_cast<const f4_t*>(&s_alpha[wave][4]);
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int d = 0; d < 8; ++d) acc[g][d] *= a[g];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float pr[GP];
+      *reinterpret_cast<f4_t*>(&pr[0]) = *reinterpret_cast<const f4_t*>(&s_p[wave][4 * j + quarter][0]);
+      if (GP > 4) *reinterpret_cast<f4_t*>(&pr[4]) = *reinterpret_cast<const f4_t*>(&s_p[wave][4 * j + quarter][4]);
+      const u32 w[4] = {vv[j].x, vv[j].y, vv[j].z, vv[j].w};
+      float vf[8];
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        vf[2 * d] = lo16<DT>(w[d]);
+        vf[2 * d + 1] = hi16<DT>(w[d]);
+      }
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int d = 0; d < 8; ++d) acc[g][d] = fmaf(pr[g], vf[d], acc[g][d]);
+    }
+    __builtin_amdgcn_wave_barrier();
+  };
+
+  {
+    // One K and one V register set: the next tile's K loads are issued as soon as this tile's K
+    // sits in LDS, the next V loads as soon as this tile's V is folded in.  Tokens run one tile
+    // further ahead.
+    int tokC[4], tokN[4];
+    v4u kk[4], vv[4];
+    int t0 = s_begin + wave * 16;  // uniform over the wave: every lane takes part in the MFMAs and DPP
+    if (t0 < s_end) {
+      load_tok(t0, tokC);
+      load_tile(t0, tokC, kk, Kp, Ks);
+      load_tile(t0, tokC, vv, Vp, Vs);
+      if (t0 + 64 < s_end) load_tok(t0 + 64, tokN);
+    }
+    for (; t0 < s_end; t0 += 64) {
+      const bool more = t0 + 64 < s_end;
+      store_fetched(t0, tokC, kk, Kp);
+      stage_k(kk);
+      if (more) load_tile(t0 + 64, tokN, kk, Kp, Ks);
+      softmax_tile(t0);
+      store_fetched(t0, tokC, vv, Vp);
+      fold_v(vv);
+      if (more) {
+        load_tile(t0 + 64, tokN, vv, Vp, Vs);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tokC[j] = tokN[j];
+        if (t0 + 128 < s_end) load_tok(t0 + 128, tokN);
       }
     }
   }
 
-  // merge the four row groups of the wave (lanes c, c+16, c+32, c+48)
+  // the four row groups of the wave hold different rows under the same maxima: add them up
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
+  for (int g = 0; g < G; ++g)
 #pragma unroll
-    for (int sh = 16; sh <= 32; sh <<= 1) {
-      const float om = __shfl_xor(mx[g], sh);
-      const float os = __shfl_xor(sum[g], sh);
-      const float mnew = fmaxf(mx[g], om);
-      const float wa = (mx[g] == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mx[g] - mnew);
-      const float wb = (om == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(om - mnew);
-      sum[g] = sum[g] * wa + os * wb;
+    for (int d = 0; d < 8; ++d) {
+      float v = acc[g][d];
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      acc[g][d] = v;
+    }
 #pragma unroll
-      for (int d = 0; d < 8; ++d) {
-        const float oa = __shfl_xor(acc[g][d], sh);
-        acc[g][d] = acc[g][d] * wa + oa * wb;
+  for (int i = 0; i < 4; ++i) lrun[i] = row16_sum(lrun[i]);
+  if (m == 0 && quarter * 4 < GP) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int g = quarter * 4 + i;
+      if (g < G) {
+        s_ml[wave][g][0] = mrun[i];
+        s_ml[wave][g][1] = lrun[i];
       }
-      mx[g] = mnew;
     }
   }
-  // merge the four waves through LDS
-  __shared__ float s_ml[4][G][2];
-  __shared__ float s_acc[4][G][kD];
-  if (r == 0) {
+  if (quarter == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      if (c == 0) {
-        s_ml[wave][g][0] = mx[g];
-        s_ml[wave][g][1] = sum[g];
-      }
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int d = 0; d < 8; ++d) s_acc[wave][g][c * 8 + d] = acc[g][d];
-    }
+      for (int d = 0; d < 8; ++d) s_acc[wave][g][m * 8 + d] = acc[g][d];
   }
   __syncthreads();
   const int b_out = p / Hkv, h_out = p % Hkv;

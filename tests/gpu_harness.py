@@ -45,7 +45,13 @@ class Parity:
         self.min_margin = np.inf
         self.filled = 0
 
-    def step(self, q_np64, tau, k, label=""):
+    def step(self, q_np64, tau, k, label="", pairs=None):
+        """One step on the GPU and in the oracle; ``pairs`` limits the comparison (and the oracle's work)
+        to those pairs for this step."""
+        if pairs is not None:
+            self.pairs = sorted(int(p) for p in pairs)
+            self.pair_mask = np.zeros(self.s.P, np.uint8)
+            self.pair_mask[self.pairs] = 1
         s = self.s
         G = s.Hq // s.Hkv
         qt = W.round_to(q_np64, self.dtype)
@@ -123,6 +129,23 @@ class Parity:
                 self.max_err = max(self.max_err, err)
                 assert err <= OUT_TOL, f"{where} head {hq}: attention max-abs error {err:.3e}"
         return r
+
+
+def make_session_on_gpu(w, flags=0, side_stream=False):
+    """A BASELINE-sized workload: K, V drawn on the GPU, copied once to pinned host memory (which
+    is both the fill source of the offload workloads and what the oracle reads)."""
+    K_dev, V_dev = W.make_kv(w.B, w.Hkv, w.N, w.D, w.dtype, w.seed, device="cuda:0")
+    K_host = torch.empty(K_dev.shape, dtype=K_dev.dtype, pin_memory=True).copy_(K_dev)
+    V_host = torch.empty(V_dev.shape, dtype=V_dev.dtype, pin_memory=True).copy_(V_dev)
+    torch.cuda.synchronize()
+    K_src = K_host if w.host_k else K_dev
+    V_src = V_host if w.host_v else V_dev
+    if w.host_v:
+        del V_dev
+    sess = Q.Session(w.B, w.Hq, w.Hkv, w.N, w.k, w.dtype, K_dev, K_src, V_src, flags=flags, side_stream=side_stream)
+    Kb = K_host.view(torch.int16).numpy().view(np.uint16)
+    Vb = V_host.view(torch.int16).numpy().view(np.uint16)
+    return sess, Kb, Kb, Vb
 
 
 def make_session(B, Hq, Hkv, N, k_max, dtype, seed=W.DEFAULT_SEED, host_k=False, host_v=False, flags=0,

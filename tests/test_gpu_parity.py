@@ -44,7 +44,8 @@ def test_tiny_config_full_run(H):
     assert 0.3 < par.n_reuse / (par.n_reuse + par.n_miss) < 0.95
 
 
-@pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_SCORE_VALU, Q.QSAC_FLAG_SERIAL, Q.QSAC_FLAG_PROFILE])
+@pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_SCORE_VALU, Q.QSAC_FLAG_PROFILE, Q.QSAC_FLAG_FILL_KERNEL,
+                                   Q.QSAC_FLAG_FILL_KERNEL | Q.QSAC_FLAG_SERIAL, Q.QSAC_FLAG_FILL_KERNEL | Q.QSAC_FLAG_PROFILE])
 def test_ragged_shapes_gqa5_bf16(H, flags):
     """N, k and k_max off every tile size (1024-key score tiles, 8192-key select chunks, 64-row
     fill and attention tiles), G = 5 as in the Qwen2.5-14B shape."""
@@ -84,9 +85,11 @@ def test_peaked_softmax_and_outlier_values(H):
     run_chain(H, B=1, Hq=8, Hkv=2, N=4000, k=512, k_max=512, dtype="bf16", steps=10, q_norm=2 * np.sqrt(128.0))
 
 
-def test_fill_from_pinned_host_memory(H):
-    run_chain(H, B=2, Hq=8, Hkv=2, N=6000, k=384, k_max=400, dtype="bf16", steps=12, host_k=True, host_v=True)
-    run_chain(H, B=1, Hq=8, Hkv=2, N=6000, k=384, k_max=384, dtype="f16", steps=8, host_v=True, side_stream=False)
+@pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_FILL_KERNEL])
+def test_fill_from_pinned_host_memory(H, flags):
+    run_chain(H, B=2, Hq=8, Hkv=2, N=6000, k=384, k_max=400, dtype="bf16", steps=12, host_k=True, host_v=True, flags=flags)
+    run_chain(H, B=1, Hq=8, Hkv=2, N=6000, k=384, k_max=384, dtype="f16", steps=8, host_v=True, side_stream=False,
+              flags=flags)
 
 
 def test_per_head_tau_and_importance(H):
@@ -96,9 +99,15 @@ def test_per_head_tau_and_importance(H):
     assert par.n_reuse > 0
 
 
-def test_many_pairs_long_rows(H):
+@pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_FILL_KERNEL])
+def test_many_pairs_long_rows(H, flags):
     """More pairs than compute-unit waves in flight, and an N that spans several select chunks."""
-    run_chain(H, B=8, Hq=16, Hkv=4, N=20000, k=640, k_max=640, dtype="bf16", steps=6)
+    run_chain(H, B=8, Hq=16, Hkv=4, N=20000, k=640, k_max=640, dtype="bf16", steps=6, flags=flags)
+
+
+def test_attention_with_several_tiles_per_wave(H):
+    """k large enough that a workgroup takes 512 slots: eight tiles per wave through the two-buffer pipeline."""
+    run_chain(H, B=4, Hq=8, Hkv=2, N=40000, k=3000, k_max=3000, dtype="bf16", steps=5, tau=0.93, expect_both=False)
 
 
 @pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_SCORE_VALU])
@@ -196,7 +205,7 @@ def test_back_to_back_steps_without_host_sync(H):
     same state as the same steps taken one at a time."""
     res = []
     for sync_each in (True, False):
-        sess, *_ = H.make_session(2, 8, 2, 7000, 256, "bf16", host_v=True)
+        sess, *_ = H.make_session(2, 8, 2, 7000, 256, "bf16", host_v=True, flags=Q.QSAC_FLAG_FILL_KERNEL)
         chain = W.QueryChain(2, 8, 128, 0.95, 22)
         qs = [W.round_to(chain.next(), "bf16").cuda() for _ in range(16)]
         torch.cuda.synchronize()
