@@ -181,7 +181,7 @@ int qsac_last_hip_error(void);
 /*
  * Stage timing, for contexts created with QSAC_FLAG_PROFILE.  The stages of a step, in launch
  * order, are: 0 "gate" (qsac_gate_kernel), 1 "score" (qsac_score_mfma_kernel or
- * qsac_score_valu_kernel), 2 "select" (qsac_select_small_kernel for N <= 131072, else
+ * qsac_score_valu_kernel), 2 "select" (qsac_select_small_kernel for N <= 65536, else
  * qsac_refine_kernel<1>, <2>, qsac_mark_kernel, qsac_diff_kernel), 3 "fill" (qsac_fill_kernel),
  * 4 "attn" (qsac_attn_kernel, qsac_combine_kernel).  qsac_get_stage_ms() waits for the last profiled step and writes
  * the summed duration of each stage in milliseconds to ms_sum[qsac_num_stages()] and the number
@@ -192,6 +192,13 @@ int qsac_last_hip_error(void);
 int qsac_num_stages(void);
 const char *qsac_stage_name(int i);
 int qsac_get_stage_ms(qsac_ctx *ctx, double *ms_sum, uint64_t *n_steps);
+
+/*
+ * Measurement aid: enqueues a plain device-to-device copy (qsac_copy_kernel) of `bytes` bytes
+ * (a multiple of 16, both pointers DEVICE and 16-byte aligned) on `stream`.  It reads `bytes` and
+ * writes `bytes`, which is what profiler memory counters are scaled against.
+ */
+int qsac_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

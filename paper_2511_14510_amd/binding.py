@@ -22,7 +22,7 @@ QSAC_MAX_GROUP, QSAC_MAX_KV_HEADS, QSAC_HEAD_DIM = 8, 64, 128
 
 EXPORTS = ("qsac_workspace_bytes", "qsac_workspace_layout", "qsac_init", "qsac_reset", "qsac_step",
            "qsac_get_stats", "qsac_free", "qsac_strerror", "qsac_last_hip_error", "qsac_num_stages",
-           "qsac_stage_name", "qsac_get_stage_ms")
+           "qsac_stage_name", "qsac_get_stage_ms", "qsac_calibration_copy")
 
 
 class qsac_config(C.Structure):
@@ -77,6 +77,7 @@ def load():
         L.qsac_stage_name.restype = C.c_char_p
         L.qsac_stage_name.argtypes = [C.c_int]
         L.qsac_get_stage_ms.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
+        L.qsac_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
 
@@ -141,6 +142,12 @@ def qsac_get_stage_ms(ctx):
     if rc:
         raise QsacError(rc, "qsac_get_stage_ms")
     return [L.qsac_stage_name(i).decode() for i in range(n)], list(ms), int(steps.value)
+
+
+def qsac_calibration_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
+    rc = load().qsac_calibration_copy(dst_ptr, src_ptr, nbytes, stream)
+    if rc:
+        raise QsacError(rc, "qsac_calibration_copy")
 
 
 def qsac_free(ctx) -> None:

@@ -387,8 +387,7 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     if (nvec <= 2 * kDiffThreads) QSAC_SELECT(2);
     else if (nvec <= 4 * kDiffThreads) QSAC_SELECT(4);
     else if (nvec <= 8 * kDiffThreads) QSAC_SELECT(8);
-    else if (nvec <= 16 * kDiffThreads) QSAC_SELECT(16);
-    else QSAC_SELECT(0);
+    else QSAC_SELECT(16);
 #undef QSAC_SELECT
   } else {
     dim3 sel_grid((unsigned)(L.n_pad / kSelChunk), (unsigned)P);
@@ -498,6 +497,15 @@ const char* qsac_strerror(int code) {
 }
 
 int qsac_last_hip_error(void) { return g_last_hip; }
+
+int qsac_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src) return QSAC_ENULL;
+  if (!aligned16(dst) || !aligned16(src) || (bytes & 15u)) return QSAC_EALIGN;
+  if (bytes == 0) return QSAC_OK;
+  qsac_copy_kernel<<<4096, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<v4u*>(dst), static_cast<const v4u*>(src), bytes / 16);
+  HIP_TRY(hipGetLastError());
+  return QSAC_OK;
+}
 
 int qsac_num_stages(void) { return kStages; }
 

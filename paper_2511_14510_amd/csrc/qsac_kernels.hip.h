@@ -33,7 +33,7 @@ constexpr int kRowU4 = 16;         // 16-byte chunks per 256-byte row
 constexpr int kBins = 2048;        // bins per radix level (level 2 uses the first 1024)
 constexpr int kScoreRowsSmall = 256;   // keys per workgroup of the scoring kernel (small-N path)
 constexpr int kScoreRowsLarge = 1024;  // ... when the level-0 histogram is fused in (large-N path)
-constexpr int kSmallMaxN = 131072;     // largest N whose three bitmaps fit in LDS (3 x 16 KiB)
+constexpr int kSmallMaxN = 65536;      // largest N the one-workgroup select takes: its keys fit in the registers of 1024 threads
 constexpr int kTilePitch = 272;        // bytes between key rows of an LDS tile: 256 + 16 keeps b128 reads conflict-free
 constexpr int kSelChunk = 8192;    // keys per workgroup of the select passes
 constexpr int kFillRows = 64;      // miss-list entries per workgroup of the fill kernel
@@ -106,17 +106,25 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave, in DPP: Kogge-Stone inside each row of 16
+// (row_shr 1, 2, 4, 8, zero-filled), then lane 15 of row 0 / 2 into rows 1 / 3, then lane 31 into
+// rows 2 and 3.  All 64 lanes must be active.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
 // Exclusive prefix sum of one int per thread over a workgroup of NW wavefronts; *total gets the sum.
 // Contains barriers: every thread of the workgroup must call it.
 template <int NW>
 __device__ __forceinline__ int block_exclusive_scan(int v, int* s_wave /*[NW+1]*/, int* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    int t = __shfl_up(inc, d);
-    if (lane >= d) inc += t;
-  }
+  const int inc = wave_inclusive_scan(v);
   __syncthreads();  // s_wave may still be read from a previous call
   if (lane == 63) s_wave[wave] = inc;
   __syncthreads();
@@ -129,6 +137,25 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* s_wave /*[NW+1]*
   }
   *total = tot;
   return base + inc - v;
+}
+
+// Exclusive prefix over the waves of a workgroup of one value per wave (the same in all its lanes).
+// Contains barriers.
+template <int NW>
+__device__ __forceinline__ int wave_totals_exclusive(int wave_value, int* s_wave, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) s_wave[wave] = wave_value;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    int t = s_wave[w];
+    if (w < wave) base += t;
+    tot += t;
+  }
+  *total = tot;
+  return base;
 }
 
 // Among bins [0, nbins) of `hist`, finds the bin b with  count(bins > b) < need <= count(bins >= b).
@@ -514,6 +541,7 @@ __global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restric
 // the workspace).  Thread t of NT owns a contiguous run of bitmap words.  nw holds the keys above
 // the k-th key on entry and the selected set on exit.
 //  A. ties: of the keys equal to the k-th key, the r with the lowest indices join the set;
+//     (the bitmaps are walked wave by wave, 64 coalesced words at a time, ranks by DPP scans)
 //  B. bitmap of the tokens cached before the step (from slot_idx);
 //  C. ascending index list, hit mask, ascending list of tokens to fetch;
 //  D. ascending list of slots whose token left the set;
@@ -525,31 +553,45 @@ __device__ __forceinline__ void diff_phases(u32* nw, const u32* eq, u32* old, bo
                                             int* __restrict__ mt, int* __restrict__ ft,
                                             int* __restrict__ miss_count_p, u32* __restrict__ valid_p,
                                             u64* __restrict__ stats, int* s_wave) {
-  const int tid = threadIdx.x;
+  constexpr int NW = NT / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // wave w owns the contiguous words [wb, we); lane l takes words wb + l, wb + l + 64, ... so that
+  // every bitmap read is coalesced and index order is (iteration, lane)
+  const int wpw = ((words + NW - 1) / NW + 63) & ~63;
+  const int wb = min(wave * wpw, words), we = min(wb + wpw, words);
   for (int j = tid; j < k; j += NT) ft[j] = -1;  // slots that keep their row; E names the others
-  const int wpt = (words + NT - 1) / NT;
-  const int w0 = min(tid * wpt, words), w1 = min(w0 + wpt, words);
   int total;
   // A
   int ceq = 0;
-  for (int w = w0; w < w1; ++w) ceq += __popc(eq[w]);
-  int rank = block_exclusive_scan<NT / 64>(ceq, s_wave, &total);
-  for (int w = w0; w < w1; ++w) {
-    u32 e = eq[w];
-    const int c = __popc(e);
-    if (rank + c > r) {  // keep only the lowest (r - rank) bits of e
-      int keep = r - rank;
-      u32 kept = 0;
-      while (keep > 0 && e) {
-        u32 low = e & (0u - e);
-        kept |= low;
-        e ^= low;
-        --keep;
-      }
-      e = kept;
+  for (int w = wb + lane; w < we; w += 64) ceq += __popc(eq[w]);
+  ceq = __shfl(wave_inclusive_scan(ceq), 63);
+  int run = wave_totals_exclusive<NW>(ceq, s_wave, &total);
+  if (total == r) {  // every key equal to the k-th key belongs to the set (the usual case: it is alone)
+    for (int w = wb + lane; w < we; w += 64) {
+      const u32 e = eq[w];
+      if (e) nw[w] |= e;
     }
-    rank += c;
-    if (e) nw[w] |= e;
+  } else {
+    for (int w0 = wb; w0 < we; w0 += 64) {
+      const int w = w0 + lane;
+      u32 e = w < we ? eq[w] : 0u;
+      const int c = __popc(e);
+      const int inc = wave_inclusive_scan(c);
+      const int rank = run + inc - c;  // keys equal to the k-th key at lower indices
+      if (c && rank + c > r) {         // keep only the lowest (r - rank) bits of e
+        int keep = r - rank;
+        u32 kept = 0;
+        while (keep > 0 && e) {
+          u32 low = e & (0u - e);
+          kept |= low;
+          e ^= low;
+          --keep;
+        }
+        e = kept;
+      }
+      if (e) nw[w] |= e;
+      run += __shfl(inc, 63);
+    }
   }
   // B
   if (was_valid)
@@ -560,31 +602,49 @@ __device__ __forceinline__ void diff_phases(u32* nw, const u32* eq, u32* old, bo
   __syncthreads();
   // C
   int cn = 0, cm = 0;
-  for (int w = w0; w < w1; ++w) {
+  for (int w = wb + lane; w < we; w += 64) {
     const u32 a = nw[w], o = old[w];
     cn += __popc(a);
     cm += __popc(a & ~o);
   }
-  int jn = block_exclusive_scan<NT / 64>(cn, s_wave, &total);
-  int jm = block_exclusive_scan<NT / 64>(cm, s_wave, &total);
-  for (int w = w0; w < w1; ++w) {
-    u32 a = nw[w];
-    const u32 o = old[w];
-    while (a) {
-      const int bit = __ffs(a) - 1;
-      a &= a - 1;
-      const int tok = w * 32 + bit;
-      const bool hit = (o >> bit) & 1u;
-      if (jn < k) {  // the set has exactly k members; the guard only protects the buffers
-        tk[jn] = tok;
-        ss[jn] = tok;
-        hm[jn] = (uint8_t)hit;
+  cn = __shfl(wave_inclusive_scan(cn), 63);
+  cm = __shfl(wave_inclusive_scan(cm), 63);
+  int runn = wave_totals_exclusive<NW>(cn, s_wave, &total);
+  int runm = wave_totals_exclusive<NW>(cm, s_wave, &total);
+  for (int w0 = wb; w0 < we; w0 += 256) {  // four coalesced rounds of loads in flight at a time
+    u32 av[4], ov[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int w = w0 + u * 64 + lane;
+      av[u] = w < we ? nw[w] : 0u;
+      ov[u] = w < we ? old[w] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      u32 a = av[u];
+      const u32 o = ov[u];
+      const int c1 = __popc(a), c2 = __popc(a & ~o);
+      const int i1 = wave_inclusive_scan(c1), i2 = wave_inclusive_scan(c2);
+      int jn = runn + i1 - c1, jm = runm + i2 - c2;
+      const int w = w0 + u * 64 + lane;
+      while (a) {
+        const int bit = __ffs(a) - 1;
+        a &= a - 1;
+        const int tok = w * 32 + bit;
+        const bool hit = (o >> bit) & 1u;
+        if (jn < k) {  // the set has exactly k members; the guard only protects the buffers
+          tk[jn] = tok;
+          ss[jn] = tok;
+          hm[jn] = (uint8_t)hit;
+        }
+        ++jn;
+        if (!hit) {
+          if (jm < k) mt[jm] = tok;
+          ++jm;
+        }
       }
-      ++jn;
-      if (!hit) {
-        if (jm < k) mt[jm] = tok;
-        ++jm;
-      }
+      runn += __shfl(i1, 63);
+      runm += __shfl(i2, 63);
     }
   }
   // D
@@ -652,10 +712,9 @@ __device__ __forceinline__ u32 or8(u32 v) {
 
 // Small-N path (N <= kSmallMaxN): one workgroup of 1024 threads per missing pair selects and
 // diffs in one go.  Three histogram passes (11 + 11 + 10 bits) pin the k-th largest key T
-// exactly; a fourth pass turns "key > T" and "key == T" into LDS bitmaps.  With VPT > 0 thread t
-// keeps key vectors t, t + 1024, ... (VPT of them, 4 keys each) in registers, so the keys are
-// read from memory once; VPT = 0 re-reads them (from L2) on every pass.  Dynamic LDS: three
-// bitmaps of bm_words words.
+// exactly; a fourth pass turns "key > T" and "key == T" into LDS bitmaps.  Thread t keeps key
+// vectors t, t + 1024, ... (VPT of them, 4 keys each) in registers, so the keys are read from
+// memory once.  Dynamic LDS: three bitmaps of bm_words words.
 template <int VPT>
 __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
     const uint8_t* __restrict__ reuse_flags, const u32* __restrict__ keys, u32* __restrict__ valid,
@@ -666,7 +725,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
   const int p = blockIdx.x;
   if (reuse_flags[p]) return;
   constexpr int NT = kDiffThreads;
-  constexpr int NV = VPT > 0 ? VPT : 1;
+  constexpr int NV = VPT;
   extern __shared__ u32 s_dyn[];
   __shared__ u32 s_hist[kBins];
   __shared__ int s_wave[17];
@@ -675,19 +734,16 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
   u32* s_eq = s_dyn + bm_words;
   u32* s_old = s_dyn + 2 * bm_words;
   const int tid = threadIdx.x;
-  const u32* kp = keys + (size_t)p * n_pad;
-  const v4u* kp4 = reinterpret_cast<const v4u*>(kp);
+  const v4u* kp4 = reinterpret_cast<const v4u*>(keys + (size_t)p * n_pad);
   const int n = (int)N;
   const int nvec = (n + 3) >> 2;  // n_pad is a multiple of 8192, so whole vectors can be read
   const int words = (n + 31) >> 5;
 
   v4u kreg[NV];
-  if (VPT > 0) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int v = tid + i * NT;
-      kreg[i] = v < nvec ? kp4[v] : v4u{0, 0, 0, 0};
-    }
+  for (int i = 0; i < NV; ++i) {
+    const int v = tid + i * NT;
+    kreg[i] = v < nvec ? kp4[v] : v4u{0, 0, 0, 0};
   }
   for (int i = tid; i < bm_words; i += NT) s_old[i] = 0;
 
@@ -710,12 +766,8 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
         if (e + i < n && match) atomicAdd(&s_hist[(ks[i] >> sub) & mask], 1u);
       }
     };
-    if (VPT > 0) {
 #pragma unroll
-      for (int i = 0; i < NV; ++i) count(kreg[i], tid + i * NT);
-    } else {
-      for (int v = tid; v < nvec; v += NT) count(kp4[v], v);
-    }
+    for (int i = 0; i < NV; ++i) count(kreg[i], tid + i * NT);
     __syncthreads();
     const int nb = level == 2 ? 1024 : kBins;
     const u32 b = (u32)find_bin<NT>(s_hist, nb, need, &above, s_wave, s_res);
@@ -742,16 +794,8 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
       s_eq[v >> 3] = q;
     }
   };
-  const int nvec8 = (nvec + 7) & ~7;  // whole groups of 8 lanes stay together for or8
-  if (VPT > 0) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) nibbles(kreg[i], tid + i * NT);
-  } else {
-    for (int v0 = 0; v0 < nvec8; v0 += NT) {  // uniform trip count: every lane takes part in or8
-      const int v = v0 + tid;
-      nibbles(v < nvec ? kp4[v] : v4u{0, 0, 0, 0}, v);
-    }
-  }
+  for (int i = 0; i < NV; ++i) nibbles(kreg[i], tid + i * NT);
   __syncthreads();
   diff_phases<NT>(s_new, s_eq, s_old, valid[p] != 0, need, words, k, slot_idx + (size_t)p * k_max,
                   set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
@@ -1098,6 +1142,12 @@ __global__ __launch_bounds__(128) void qsac_combine_kernel(const float* __restri
 // Clears `n` 32-bit words (used instead of a memset node so that the step can be captured in a graph).
 __global__ __launch_bounds__(256) void qsac_zero_kernel(u32* __restrict__ ptr, size_t n) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) ptr[i] = 0;
+}
+
+// Plain 16-byte-per-lane copy of n vectors: the known-size kernel that hardware counters are
+// calibrated against.
+__global__ __launch_bounds__(256) void qsac_copy_kernel(v4u* __restrict__ dst, const v4u* __restrict__ src, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
 }  // namespace qsac

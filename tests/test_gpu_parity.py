@@ -116,8 +116,34 @@ def test_large_n_path(H, flags):
     run_chain(H, B=1, Hq=8, Hkv=2, N=140001, k=700, k_max=700, dtype="bf16", steps=6, flags=flags, tau=0.93)
 
 
-def test_small_path_at_its_largest_n(H):
-    run_chain(H, B=1, Hq=5, Hkv=1, N=131072, k=1000, k_max=1000, dtype="bf16", steps=4, tau=0.93, expect_both=False)
+@pytest.mark.parametrize("N", [65536, 65537])
+def test_both_sides_of_the_select_switch(H, N):
+    run_chain(H, B=1, Hq=5, Hkv=1, N=N, k=1000, k_max=1000, dtype="bf16", steps=4, tau=0.93, expect_both=False)
+
+
+def test_ties_across_many_waves_of_the_bitmap(H):
+    """Half the keys are one repeated row: thousands of keys equal the k-th key, spread over every wave's
+    share of the bitmap, so the ranked tie resolution (not the all-ties-belong shortcut) decides the set."""
+    B, Hq, Hkv, N = 1, 4, 1, 70000
+    g = torch.Generator().manual_seed(5)
+    K = torch.randn((B, Hkv, N, 128), generator=g)
+    K[:, :, 1::2] = K[0, 0, 1]
+    K = K.to(torch.bfloat16)
+    V = torch.randn((B, Hkv, N, 128), generator=g).to(torch.bfloat16)
+    for n_ctx, k in ((N, 30000), (40000, 15000)):
+        sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, n_ctx, k, "bf16", K=K[:, :, :n_ctx].contiguous(),
+                                            V=V[:, :, :n_ctx].contiguous())
+        par = H.Parity(sess, "bf16", Kb, Ksb, Vsb)
+        # queries along the repeated row: its score is positive and in the upper half, so the
+        # k-th score is that of the repeated row itself
+        base = K[0, 0, 1].double().numpy()
+        rng = np.random.default_rng(3)
+        for t in range(3):
+            q = np.tile(base / np.linalg.norm(base), (B, Hq, 1)) + 0.02 * rng.standard_normal((B, Hq, 128))
+            r = par.step(q, 2.0, k, label=f"mass ties N={n_ctx} step {t}")
+            assert (r.scores[0] == r.kth_score[0]).sum() > 1000
+        assert par.n_band == 0
+        sess.close()
 
 
 def exact_tie_case(H, flags):
