@@ -20,6 +20,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes the scoring kernel moves per missing pair, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (profiles/qsac_step_kernels__llama3_8b_32k_all_miss__pmc_{fetch,write}_size.txt): per launch of 64 missing
+# pairs FETCH_SIZE = 262428.6 units of 2.000 KiB and WRITE_SIZE = 8245.5 units of 1.000 KiB (units calibrated
+# against the 256-MiB qsac_copy_kernel of the same runs).  bench.py cannot collect counters itself.
+PMC_SCORE_BYTES_PER_MISSING_PAIR = {"llama3_8b_32k": (262428.6 * 2.000 + 8245.5 * 1.000) * 1024 / 64}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -174,7 +180,9 @@ def main():
         r = roof(us, dd, K_steps)
         sc = r["score"]
         result["roofline"] = {"bound": "hbm", "kernel": names[1], "achieved": sc["achieved"], "peak": HBM_PEAK_GBS,
-                              "unit": "GB/s", "frac": sc["achieved"] / HBM_PEAK_GBS, "traffic": None,
+                              "unit": "GB/s", "frac": sc["achieved"] / HBM_PEAK_GBS,
+                              "traffic": (PMC_SCORE_BYTES_PER_MISSING_PAIR[w.name] * sc["missing_pairs_per_launch"]
+                                          if w.name in PMC_SCORE_BYTES_PER_MISSING_PAIR and not a.flags else None),
                               "bytes_per_launch": sc["bytes_per_launch"], "us_per_launch": sc["us_per_launch"],
                               "missing_pairs_per_launch": sc["missing_pairs_per_launch"]}
         result["stage_us"] = dict(zip(names, [round(x, 2) for x in us]))
