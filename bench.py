@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--workload", default="llama3_8b_32k")
     ap.add_argument("--tau", type=float, default=None, help="override the workload's threshold")
     ap.add_argument("--flags", type=int, default=0, help="extra qsac_config.flags (e.g. 4 = ALU scoring)")
+    ap.add_argument("--side-stream", action="store_true",
+                    help="give the library a second stream (attention of reused heads, or the fill kernel, runs on it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the stage-timing passes")
     ap.add_argument("--calibration-copies", type=int, default=0,
@@ -112,7 +114,7 @@ def main():
 
     def session(flags):
         return Q.Session(w.B, w.Hq, w.Hkv, w.N, w.k, w.dtype, K_dev, K_src, V_src, flags=flags | a.flags,
-                         side_stream=bool(a.flags & Q.QSAC_FLAG_FILL_KERNEL))
+                         side_stream=bool(a.side_stream))
 
     # ---- timed run: K steps after W warmup steps, overlapped fill, no events inside
     sess = session(0)
@@ -142,7 +144,9 @@ def main():
                    "K_fill_source": "pinned host" if w.host_k else "HBM",
                    "V_fill_source": "pinned host" if w.host_v else "HBM",
                    "scoring": "alu" if (a.flags & Q.QSAC_FLAG_SCORE_VALU) else "mfma",
-                   "fill": "own kernel on a side stream" if (a.flags & Q.QSAC_FLAG_FILL_KERNEL) else "folded into attention loads"},
+                   "fill": "own kernel on a side stream" if (a.flags & Q.QSAC_FLAG_FILL_KERNEL) else "folded into attention loads",
+                   "side_stream": (("fill kernel" if (a.flags & Q.QSAC_FLAG_FILL_KERNEL) else "attention of reused heads")
+                                   if a.side_stream else None)},
         "reuse_rate": reuse_rate, "slot_hit_rate": slot_hit_rate,
         "rows_filled_per_step": d["slot_misses"] / K_steps,
     }

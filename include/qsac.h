@@ -63,7 +63,7 @@ enum {
 /* qsac_config.flags */
 enum {
   QSAC_FLAG_DRY_RUN = 1,     /* validate only: the ctx never touches a device (for hosts without a GPU) */
-  QSAC_FLAG_SERIAL = 2,      /* with QSAC_FLAG_FILL_KERNEL: fill on stream_main even when stream_side is given */
+  QSAC_FLAG_SERIAL = 2,      /* run everything on stream_main even when stream_side is given              */
   QSAC_FLAG_SCORE_VALU = 4,  /* score with packed dot-product ALU ops instead of the MFMA tile           */
   QSAC_FLAG_PROFILE = 8,     /* bracket every stage with timing events (single stream; see qsac_get_stage_ms) */
   QSAC_FLAG_FILL_KERNEL = 16 /* fill the missing rows with a kernel of its own (on stream_side if given, overlapped
@@ -75,12 +75,14 @@ typedef struct qsac_ctx qsac_ctx;
 
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim must be 128; n_q_heads % n_kv_heads == 0 */
-  int64_t n_ctx;                /* N, fixed for the life of the ctx; 1 <= N <= 2^24                      */
+  int64_t n_ctx;                /* N, fixed for the life of the ctx; 1 <= N <= 2^20                      */
   int32_t k_max;                /* slot stride of the cache tensors; 1 <= k <= k_max <= N                */
   int32_t dtype;                /* QSAC_F16 | QSAC_BF16: type of q, K, V, prev_q and the slots           */
   const float *q_head_importance; /* HOST, [n_q_heads] weights s_j of Eq. (2), all > 0; NULL = all 1     */
   void *stream_main;            /* hipStream_t (NULL = default stream); borrowed                          */
-  void *stream_side;            /* hipStream_t for the fill kernel (QSAC_FLAG_FILL_KERNEL), or NULL; borrowed */
+  void *stream_side;            /* second hipStream_t or NULL; borrowed.  Given one, the attention of the heads that
+                                   reused runs on it beside the select (with QSAC_FLAG_FILL_KERNEL: the fill kernel
+                                   runs on it beside that attention).  The step still completes on stream_main. */
   void *workspace;              /* DEVICE, 256-byte aligned, >= qsac_workspace_bytes(); caller-owned       */
   size_t workspace_bytes;
   int32_t flags;
@@ -192,6 +194,22 @@ int qsac_last_hip_error(void);
 int qsac_num_stages(void);
 const char *qsac_stage_name(int i);
 int qsac_get_stage_ms(qsac_ctx *ctx, double *ms_sum, uint64_t *n_steps);
+
+/*
+ * Adaptive per-head thresholds, Section 4.3, Eq. (3)-(5) (pure host function, fp64 inside):
+ *   theta* = arccos(eta);  theta_i = lambda_i theta* + (1 - lambda_i) pi;  tau_i = cos(theta_i);  lambda_i = s_i^p
+ * importance[n] are head importance scores s_i in [0, 1] (one per KV head when the result feeds
+ * qsac_step_args.tau), eta in [-1, 1] the upper bound of the thresholds, p > 0 (the paper uses eta = 0.8,
+ * p = 3).  tau_out[n] receives the thresholds.  QSAC_EINVAL for values outside those ranges.
+ */
+int qsac_adaptive_thresholds(const float *importance, int32_t n, float eta, float p, float *tau_out);
+
+/*
+ * Reuse difficulty of Section 4.4 (pure host function): D_i = tau_i - (avg_sim_i - eps), where avg_sim_i is
+ * the head's profiled average cosine similarity of adjacent queries and eps > 0 a tolerance margin.  The
+ * heads with the largest D_i are the candidates for resident caching.
+ */
+int qsac_reuse_difficulty(const float *tau, const float *avg_sim, int32_t n, float eps, float *d_out);
 
 /*
  * Measurement aid: enqueues a plain device-to-device copy (qsac_copy_kernel) of `bytes` bytes

@@ -22,7 +22,8 @@ QSAC_MAX_GROUP, QSAC_MAX_KV_HEADS, QSAC_HEAD_DIM = 8, 64, 128
 
 EXPORTS = ("qsac_workspace_bytes", "qsac_workspace_layout", "qsac_init", "qsac_reset", "qsac_step",
            "qsac_get_stats", "qsac_free", "qsac_strerror", "qsac_last_hip_error", "qsac_num_stages",
-           "qsac_stage_name", "qsac_get_stage_ms", "qsac_calibration_copy")
+           "qsac_stage_name", "qsac_get_stage_ms", "qsac_calibration_copy", "qsac_adaptive_thresholds",
+           "qsac_reuse_difficulty")
 
 
 class qsac_config(C.Structure):
@@ -78,6 +79,9 @@ def load():
         L.qsac_stage_name.argtypes = [C.c_int]
         L.qsac_get_stage_ms.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
         L.qsac_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        fp = C.POINTER(C.c_float)
+        L.qsac_adaptive_thresholds.argtypes = [fp, C.c_int32, C.c_float, C.c_float, fp]
+        L.qsac_reuse_difficulty.argtypes = [fp, fp, C.c_int32, C.c_float, fp]
         _lib = L
     return _lib
 
@@ -150,6 +154,30 @@ def qsac_calibration_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int =
         raise QsacError(rc, "qsac_calibration_copy")
 
 
+def _floats(xs):
+    return (C.c_float * len(xs))(*[float(x) for x in xs])
+
+
+def qsac_adaptive_thresholds(importance, eta: float, p: float) -> list:
+    """Eq. (3)-(5): per-head thresholds from head importance scores."""
+    n = len(importance)
+    out = (C.c_float * n)()
+    rc = load().qsac_adaptive_thresholds(_floats(importance), n, eta, p, out)
+    if rc:
+        raise QsacError(rc, "qsac_adaptive_thresholds")
+    return list(out)
+
+
+def qsac_reuse_difficulty(tau, avg_sim, eps: float) -> list:
+    """Section 4.4: D_i = tau_i - (avg_sim_i - eps)."""
+    n = len(tau)
+    out = (C.c_float * n)()
+    rc = load().qsac_reuse_difficulty(_floats(tau), _floats(avg_sim), n, eps, out)
+    if rc:
+        raise QsacError(rc, "qsac_reuse_difficulty")
+    return list(out)
+
+
 def qsac_free(ctx) -> None:
     rc = load().qsac_free(ctx)
     if rc:
@@ -175,7 +203,7 @@ class Session:
     """
 
     def __init__(self, B, Hq, Hkv, N, k_max, dtype: str, K_dev, K_src, V_src, flags=0, importance=None,
-                 side_stream=True):
+                 side_stream=False):
         import torch
         from .workload import DTYPE_CODES, TORCH_DTYPES
         assert torch.cuda.is_available(), "QSAC needs a GPU: there is no CPU path"

@@ -32,7 +32,7 @@ int check_config(const qsac_config* c) {
   if (c->n_kv_heads > QSAC_MAX_KV_HEADS) return QSAC_ERANGE;
   if (c->n_q_heads % c->n_kv_heads != 0) return QSAC_EINVAL;
   if (c->n_q_heads / c->n_kv_heads > QSAC_MAX_GROUP) return QSAC_ERANGE;
-  if (c->n_ctx < 1 || c->n_ctx > (int64_t(1) << 24)) return QSAC_ERANGE;
+  if (c->n_ctx < 1 || c->n_ctx > (int64_t(1) << 20)) return QSAC_ERANGE;
   if (c->k_max < 1 || c->k_max > c->n_ctx) return QSAC_ERANGE;
   if ((int64_t)c->batch * c->n_kv_heads > 65535) return QSAC_ERANGE;  // grid.y
   if (c->flags & ~(QSAC_FLAG_DRY_RUN | QSAC_FLAG_SERIAL | QSAC_FLAG_SCORE_VALU | QSAC_FLAG_PROFILE | QSAC_FLAG_FILL_KERNEL)) return QSAC_EINVAL;
@@ -170,19 +170,19 @@ void launch_score(const qsac_ctx* c, const qsac_step_args* a, u32* keys, u32* hi
 }
 
 template <int DT, int G>
-void launch_attn(const qsac_ctx* c, const qsac_step_args* a, dim3 grid, const int* fetch_tok, const int* miss_count,
-                 float* part_ml, float* part_acc, int rows, int n_splits, int which) {
+void launch_attn(const qsac_ctx* c, const qsac_step_args* a, hipStream_t stream, dim3 grid, const int* fetch_tok,
+                 const int* miss_count, float* part_ml, float* part_acc, int rows, int n_splits, int which) {
   auto q = static_cast<const uint16_t*>(a->q);
   auto Ks = static_cast<v4u*>(a->K_slots);
   auto Vs = static_cast<v4u*>(a->V_slots);
   auto Kf = static_cast<const v4u*>(a->K_src);
   auto Vf = static_cast<const v4u*>(a->V_src);
   if (c->fill_kernel)
-    qsac_attn_kernel<DT, G, false><<<grid, 256, 0, c->s_main>>>(
+    qsac_attn_kernel<DT, G, false><<<grid, 256, 0, stream>>>(
         q, Ks, Vs, Kf, Vf, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads,
         c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits, which);
   else
-    qsac_attn_kernel<DT, G, true><<<grid, 256, 0, c->s_main>>>(
+    qsac_attn_kernel<DT, G, true><<<grid, 256, 0, stream>>>(
         q, Ks, Vs, Kf, Vf, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads,
         c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits, which);
 }
@@ -253,8 +253,7 @@ int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
   c->s_main = static_cast<hipStream_t>(cfg->stream_main);
   c->s_side = static_cast<hipStream_t>(cfg->stream_side);
   c->fill_kernel = (cfg->flags & QSAC_FLAG_FILL_KERNEL) != 0;
-  c->overlap = c->fill_kernel && cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main &&
-               !(cfg->flags & QSAC_FLAG_SERIAL);
+  c->overlap = cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main && !(cfg->flags & QSAC_FLAG_SERIAL);
   c->profile = (cfg->flags & QSAC_FLAG_PROFILE) != 0;
   if (c->profile) c->overlap = false;  // stage times are taken on one stream
   c->k_bound = 0;
@@ -370,20 +369,50 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     qsac_gate_kernel<1><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
                                            a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max);
+  const int rows = attn_rows(P, k);
+  const int n_splits = (k + rows - 1) / rows;
+  dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
+  dim3 attn_grid((unsigned)n_splits, (unsigned)P);
+  auto fill_on = [&](hipStream_t s) {
+    qsac_fill_kernel<<<fill_grid, 256, 0, s>>>(miss_count, miss_slot, miss_tok, static_cast<const v4u*>(a->K_src),
+                                               static_cast<const v4u*>(a->V_src), static_cast<v4u*>(a->K_slots),
+                                               static_cast<v4u*>(a->V_slots), N, k_max);
+  };
+  auto attend = [&](hipStream_t s, int which) {
+    QSAC_DISPATCH(launch_attn, c, a, s, attn_grid, fetch_tok, miss_count, part_ml, part_acc, rows, n_splits, which);
+  };
+  auto combine = [&]() {
+    if (n_splits > 1)
+      qsac_combine_kernel<<<P * G, 128, 0, sm>>>(part_ml, part_acc, a->reuse_flags, a->out, Hq, Hkv, G, n_splits,
+                                                 L.max_splits, 0);
+  };
+  const bool side_attn = c->overlap && !c->fill_kernel;  // reused heads are attended to beside the select
+  const bool side_fill = c->overlap && c->fill_kernel;   // the fill kernel runs beside their attention
+
   // 2. scores of the missing pairs
   mark(1);
   QSAC_DISPATCH(launch_score, c, a, keys, hist);
+  if (side_attn) {
+    // The heads that reused need nothing from the miss path.  Their attention starts on the side stream once
+    // the scoring pass has had the memory system to itself, and runs beside the select, which is latency
+    // bound on a few compute units.
+    HIP_TRY(hipEventRecord(c->ev_sel, sm));
+    HIP_TRY(hipStreamWaitEvent(c->s_side, c->ev_sel, 0));
+    attend(c->s_side, 1);
+    HIP_TRY(hipEventRecord(c->ev_fill, c->s_side));
+  }
   // 3. select the k best, diff against the cache slots
   mark(2);
   if (c->small) {
-    // key vectors per thread that keep the pair's keys in registers (0: re-read them from L2)
+    // key vectors per thread that keep the pair's keys in registers
     const int64_t nvec = (N + 3) / 4;
     const int bm_words = (int)((N + 63) / 64 * 2);
     const size_t lds = (size_t)bm_words * 3 * sizeof(u32);
 #define QSAC_SELECT(VPT)                                                                                          \
   qsac_select_small_kernel<VPT><<<P, kDiffThreads, lds, sm>>>(a->reuse_flags, keys, valid, a->slot_idx, set_sorted, \
                                                              a->topk_idx, a->hit_mask, miss_count, miss_slot,      \
-                                                             miss_tok, fetch_tok, stats, N, L.n_pad, k, k_max, bm_words)
+                                                             miss_tok, fetch_tok, stats, N, L.n_pad, k, k_max,     \
+                                                             bm_words)
     if (nvec <= 2 * kDiffThreads) QSAC_SELECT(2);
     else if (nvec <= 4 * kDiffThreads) QSAC_SELECT(4);
     else if (nvec <= 8 * kDiffThreads) QSAC_SELECT(8);
@@ -395,43 +424,35 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     qsac_refine_kernel<2><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
     qsac_mark_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, bm_new, bm_eq, bm_old, sel_r, N, L.n_pad,
                                               L.words, k);
-    qsac_diff_kernel<<<P, kDiffThreads, 0, sm>>>(a->reuse_flags, valid, bm_new, bm_eq, bm_old, sel_r, a->slot_idx,
-                                                set_sorted, a->topk_idx, a->hit_mask, miss_count, miss_slot,
-                                                miss_tok, fetch_tok, stats, L.words, k, k_max);
+    // bitmap words per lane of the 1024-thread diff: 8 up to 262144 keys, 32 up to 2^20
+#define QSAC_DIFF(WPL)                                                                                             \
+  qsac_diff_kernel<WPL><<<P, kDiffThreads, 0, sm>>>(a->reuse_flags, valid, bm_new, bm_eq, bm_old, sel_r, a->slot_idx, \
+                                                   set_sorted, a->topk_idx, a->hit_mask, miss_count, miss_slot,     \
+                                                   miss_tok, fetch_tok, stats, L.words, k, k_max)
+    if (L.words <= 8 * kDiffThreads) QSAC_DIFF(8);
+    else QSAC_DIFF(32);
+#undef QSAC_DIFF
   }
   // 4. fill the missing rows (own kernel, or folded into the attention kernel's loads); 5. attention
-  const int rows = attn_rows(P, k);
-  const int n_splits = (k + rows - 1) / rows;
-  dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
-  dim3 attn_grid((unsigned)n_splits, (unsigned)P);
-  auto fill_on = [&](hipStream_t s) {
-    qsac_fill_kernel<<<fill_grid, 256, 0, s>>>(miss_count, miss_slot, miss_tok, static_cast<const v4u*>(a->K_src),
-                                               static_cast<const v4u*>(a->V_src), static_cast<v4u*>(a->K_slots),
-                                               static_cast<v4u*>(a->V_slots), N, k_max);
-  };
-  auto attend = [&](int which) {
-    QSAC_DISPATCH(launch_attn, c, a, attn_grid, fetch_tok, miss_count, part_ml, part_acc, rows, n_splits, which);
-  };
-  auto combine = [&]() {
-    if (n_splits > 1)
-      qsac_combine_kernel<<<P * G, 128, 0, sm>>>(part_ml, part_acc, a->reuse_flags, a->out, Hq, Hkv, G, n_splits,
-                                                 L.max_splits, 0);
-  };
-  if (c->overlap) {
+  if (side_attn) {
+    attend(sm, 2);
+    HIP_TRY(hipStreamWaitEvent(sm, c->ev_fill, 0));
+    combine();
+  } else if (side_fill) {
     // the fill runs on the side stream while the pairs that reused their cache are attended to
     HIP_TRY(hipEventRecord(c->ev_sel, sm));
     HIP_TRY(hipStreamWaitEvent(c->s_side, c->ev_sel, 0));
     fill_on(c->s_side);
     HIP_TRY(hipEventRecord(c->ev_fill, c->s_side));
-    attend(1);
+    attend(sm, 1);
     HIP_TRY(hipStreamWaitEvent(sm, c->ev_fill, 0));
-    attend(2);
+    attend(sm, 2);
     combine();
   } else {
     mark(3);
     if (c->fill_kernel) fill_on(sm);
     mark(4);
-    attend(0);
+    attend(sm, 0);
     combine();
     mark(5);
     c->prof_pending = c->profile;
@@ -497,6 +518,30 @@ const char* qsac_strerror(int code) {
 }
 
 int qsac_last_hip_error(void) { return g_last_hip; }
+
+int qsac_adaptive_thresholds(const float* importance, int32_t n, float eta, float p, float* tau_out) {
+  if (!importance || !tau_out) return QSAC_ENULL;
+  if (n < 0) return QSAC_ERANGE;
+  if (!(eta >= -1.f && eta <= 1.f) || !(p > 0.f) || !std::isfinite(p)) return QSAC_EINVAL;
+  for (int i = 0; i < n; ++i)
+    if (!(importance[i] >= 0.f && importance[i] <= 1.f)) return QSAC_EINVAL;
+  const double pi = 3.14159265358979323846;
+  const double theta_star = std::acos((double)eta);
+  for (int i = 0; i < n; ++i) {
+    const double lambda = std::pow((double)importance[i], (double)p);
+    const double theta = lambda * theta_star + (1.0 - lambda) * pi;
+    tau_out[i] = (float)std::cos(theta);
+  }
+  return QSAC_OK;
+}
+
+int qsac_reuse_difficulty(const float* tau, const float* avg_sim, int32_t n, float eps, float* d_out) {
+  if (!tau || !avg_sim || !d_out) return QSAC_ENULL;
+  if (n < 0) return QSAC_ERANGE;
+  if (!(eps > 0.f) || !std::isfinite(eps)) return QSAC_EINVAL;
+  for (int i = 0; i < n; ++i) d_out[i] = (float)((double)tau[i] - ((double)avg_sim[i] - (double)eps));
+  return QSAC_OK;
+}
 
 int qsac_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src) return QSAC_ENULL;

@@ -217,10 +217,14 @@ __global__ __launch_bounds__(256) void qsac_gate_kernel(
   const int b = p / Hkv, h = p % Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   __shared__ double s_sim[8];
+  __shared__ double s_imp[8];
   __shared__ int s_reuse;
   const size_t head0 = (size_t)b * Hq + (size_t)h * G;
   const u32* q32 = reinterpret_cast<const u32*>(q) + head0 * (kD / 2);
   u32* pq32 = reinterpret_cast<u32*>(prev_q) + head0 * (kD / 2);
+  // everything the decision needs is requested up front, so the kernel pays one memory round trip
+  const u32 was_valid = valid[p];
+  if (threadIdx.x < G) s_imp[threadIdx.x] = importance[h * G + threadIdx.x];
 
   for (int g = wave; g < G; g += 4) {
     u32 a = q32[g * 64 + lane], c = pq32[g * 64 + lane];
@@ -244,14 +248,14 @@ __global__ __launch_bounds__(256) void qsac_gate_kernel(
     double num = 0.0, den = 0.0;
     bool nonpos = false;
     for (int g = 0; g < G; ++g) {
-      double w = importance[h * G + g];
+      double w = s_imp[g];
       double s = s_sim[g];
       if (s <= 0.0) nonpos = true;
       num += w;
       den += w / s;
     }
     double agg = nonpos ? -1.0 : num / den;
-    int reuse = (valid[p] != 0) && (agg >= (double)tau.v[h]);
+    int reuse = (was_valid != 0) && (agg >= (double)tau.v[h]);
     s_reuse = reuse;
     reuse_flags[p] = (uint8_t)reuse;
     atomicAdd(&stats[reuse ? 1 : 2], 1ull);
@@ -541,13 +545,15 @@ __global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restric
 // the workspace).  Thread t of NT owns a contiguous run of bitmap words.  nw holds the keys above
 // the k-th key on entry and the selected set on exit.
 //  A. ties: of the keys equal to the k-th key, the r with the lowest indices join the set;
-//     (the bitmaps are walked wave by wave, 64 coalesced words at a time, ranks by DPP scans)
+//     (the bitmaps are walked wave by wave, 64 coalesced words at a time, ranks by DPP scans;
+//     WPL bounds the words a lane holds: words <= 64 * WPL * NT / 64)
 //  B. bitmap of the tokens cached before the step (from slot_idx);
 //  C. ascending index list, hit mask, ascending list of tokens to fetch;
 //  D. ascending list of slots whose token left the set;
 //  E. the i-th such slot takes the i-th token to fetch (slot table and fetch_tok).
-template <int NT>
-__device__ __forceinline__ void diff_phases(u32* nw, const u32* eq, u32* old, bool was_valid, int r, int words,
+template <int NT, int WPL>
+__device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __restrict__ eq,
+                                            u32* __restrict__ old, bool was_valid, int r, int words,
                                             int k, int* __restrict__ sl, int* __restrict__ ss,
                                             int* __restrict__ tk, uint8_t* __restrict__ hm, int* __restrict__ ms,
                                             int* __restrict__ mt, int* __restrict__ ft,
@@ -555,42 +561,51 @@ __device__ __forceinline__ void diff_phases(u32* nw, const u32* eq, u32* old, bo
                                             u64* __restrict__ stats, int* s_wave) {
   constexpr int NW = NT / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // wave w owns the contiguous words [wb, we); lane l takes words wb + l, wb + l + 64, ... so that
-  // every bitmap read is coalesced and index order is (iteration, lane)
+  // Wave w owns the contiguous words [wb, we); lane l takes words wb + l, wb + l + 64, ... (at most
+  // WPL of them), so that every bitmap read is coalesced and index order is (round, lane).  A lane
+  // keeps its words in registers: each bitmap is read from memory once, in one round trip.
   const int wpw = ((words + NW - 1) / NW + 63) & ~63;
   const int wb = min(wave * wpw, words), we = min(wb + wpw, words);
+  const int rounds = wpw >> 6;  // <= WPL, uniform over the workgroup
   for (int j = tid; j < k; j += NT) ft[j] = -1;  // slots that keep their row; E names the others
   int total;
   // A
+  u32 ev[WPL];
   int ceq = 0;
-  for (int w = wb + lane; w < we; w += 64) ceq += __popc(eq[w]);
+#pragma unroll
+  for (int u = 0; u < WPL; ++u) {
+    const int w = wb + u * 64 + lane;
+    ev[u] = (u < rounds && w < we) ? eq[w] : 0u;
+    ceq += __popc(ev[u]);
+  }
   ceq = __shfl(wave_inclusive_scan(ceq), 63);
   int run = wave_totals_exclusive<NW>(ceq, s_wave, &total);
   if (total == r) {  // every key equal to the k-th key belongs to the set (the usual case: it is alone)
-    for (int w = wb + lane; w < we; w += 64) {
-      const u32 e = eq[w];
-      if (e) nw[w] |= e;
-    }
+#pragma unroll
+    for (int u = 0; u < WPL; ++u)
+      if (ev[u]) nw[wb + u * 64 + lane] |= ev[u];
   } else {
-    for (int w0 = wb; w0 < we; w0 += 64) {
-      const int w = w0 + lane;
-      u32 e = w < we ? eq[w] : 0u;
-      const int c = __popc(e);
-      const int inc = wave_inclusive_scan(c);
-      const int rank = run + inc - c;  // keys equal to the k-th key at lower indices
-      if (c && rank + c > r) {         // keep only the lowest (r - rank) bits of e
-        int keep = r - rank;
-        u32 kept = 0;
-        while (keep > 0 && e) {
-          u32 low = e & (0u - e);
-          kept |= low;
-          e ^= low;
-          --keep;
+#pragma unroll
+    for (int u = 0; u < WPL; ++u) {
+      if (u < rounds) {  // uniform: every lane takes part in the scan
+        u32 e = ev[u];
+        const int c = __popc(e);
+        const int inc = wave_inclusive_scan(c);
+        const int rank = run + inc - c;  // keys equal to the k-th key at lower indices
+        if (c && rank + c > r) {         // keep only the lowest (r - rank) bits of e
+          int keep = r - rank;
+          u32 kept = 0;
+          while (keep > 0 && e) {
+            u32 low = e & (0u - e);
+            kept |= low;
+            e ^= low;
+            --keep;
+          }
+          e = kept;
         }
-        e = kept;
+        if (e) nw[wb + u * 64 + lane] |= e;
+        run += __shfl(inc, 63);
       }
-      if (e) nw[w] |= e;
-      run += __shfl(inc, 63);
     }
   }
   // B
@@ -601,32 +616,30 @@ __device__ __forceinline__ void diff_phases(u32* nw, const u32* eq, u32* old, bo
     }
   __syncthreads();
   // C
+  u32 av[WPL], ov[WPL];
   int cn = 0, cm = 0;
-  for (int w = wb + lane; w < we; w += 64) {
-    const u32 a = nw[w], o = old[w];
-    cn += __popc(a);
-    cm += __popc(a & ~o);
+#pragma unroll
+  for (int u = 0; u < WPL; ++u) {
+    const int w = wb + u * 64 + lane;
+    const bool in = u < rounds && w < we;
+    av[u] = in ? nw[w] : 0u;
+    ov[u] = in ? old[w] : 0u;
+    cn += __popc(av[u]);
+    cm += __popc(av[u] & ~ov[u]);
   }
   cn = __shfl(wave_inclusive_scan(cn), 63);
   cm = __shfl(wave_inclusive_scan(cm), 63);
   int runn = wave_totals_exclusive<NW>(cn, s_wave, &total);
   int runm = wave_totals_exclusive<NW>(cm, s_wave, &total);
-  for (int w0 = wb; w0 < we; w0 += 256) {  // four coalesced rounds of loads in flight at a time
-    u32 av[4], ov[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int w = w0 + u * 64 + lane;
-      av[u] = w < we ? nw[w] : 0u;
-      ov[u] = w < we ? old[w] : 0u;
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
+  for (int u = 0; u < WPL; ++u) {
+    if (u < rounds) {
       u32 a = av[u];
       const u32 o = ov[u];
       const int c1 = __popc(a), c2 = __popc(a & ~o);
       const int i1 = wave_inclusive_scan(c1), i2 = wave_inclusive_scan(c2);
       int jn = runn + i1 - c1, jm = runm + i2 - c2;
-      const int w = w0 + u * 64 + lane;
+      const int w = wb + u * 64 + lane;
       while (a) {
         const int bit = __ffs(a) - 1;
         a &= a - 1;
@@ -685,6 +698,8 @@ __device__ __forceinline__ void diff_phases(u32* nw, const u32* eq, u32* old, bo
 }
 
 // Large-N path: one workgroup per missing pair, bitmaps in the workspace (made by qsac_mark_kernel).
+// WPL: bitmap words a lane holds; words <= 1024 * WPL.
+template <int WPL>
 __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
     const uint8_t* __restrict__ reuse_flags, u32* __restrict__ valid, u32* __restrict__ bm_new,
     const u32* __restrict__ bm_eq, u32* __restrict__ bm_old, const int* __restrict__ sel_r,
@@ -695,7 +710,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
   const int p = blockIdx.x;
   if (reuse_flags[p]) return;
   __shared__ int s_wave[17];
-  diff_phases<kDiffThreads>(bm_new + (size_t)p * words, bm_eq + (size_t)p * words, bm_old + (size_t)p * words,
+  diff_phases<kDiffThreads, WPL>(bm_new + (size_t)p * words, bm_eq + (size_t)p * words, bm_old + (size_t)p * words,
                             valid[p] != 0, sel_r[p], words, k, slot_idx + (size_t)p * k_max,
                             set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
                             miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max,
@@ -797,7 +812,8 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
 #pragma unroll
   for (int i = 0; i < NV; ++i) nibbles(kreg[i], tid + i * NT);
   __syncthreads();
-  diff_phases<NT>(s_new, s_eq, s_old, valid[p] != 0, need, words, k, slot_idx + (size_t)p * k_max,
+  // 65536 keys = 2048 words = 2 per lane
+  diff_phases<NT, 2>(s_new, s_eq, s_old, valid[p] != 0, need, words, k, slot_idx + (size_t)p * k_max,
                   set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
                   miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max, fetch_tok + (size_t)p * k_max,
                   miss_count + p, valid + p, stats, s_wave);

@@ -63,7 +63,7 @@ def test_workspace_size_and_layout(lib):
     (dict(Hq=18), Q.QSAC_ERANGE),         # G = 9 > 8
     (dict(B=0), Q.QSAC_ERANGE),
     (dict(N=0), Q.QSAC_ERANGE),
-    (dict(N=(1 << 24) + 1), Q.QSAC_ERANGE),
+    (dict(N=(1 << 20) + 1), Q.QSAC_ERANGE),
     (dict(k_max=0), Q.QSAC_ERANGE),
     (dict(k_max=4097), Q.QSAC_ERANGE),    # k_max > N
     (dict(Hkv=65, Hq=65), Q.QSAC_ERANGE),
@@ -147,3 +147,36 @@ def test_strerror_and_stage_names(lib):
 def test_binding_has_no_cpu_fallback():
     src = open(os.path.join(ROOT, "paper_2511_14510_amd", "binding.py")).read()
     assert "oracle" not in src.replace("no other implementation", "")
+
+
+def test_adaptive_thresholds_match_the_oracle_and_the_closed_forms(lib, oracle):
+    import numpy as np
+    rng = np.random.default_rng(0)
+    for eta, p in ((0.8, 3.0), (0.5, 2.0), (-0.25, 1.0), (1.0, 3.0), (-1.0, 2.0)):
+        s = np.concatenate([[0.0, 1.0, 0.5], rng.uniform(0, 1, 20)]).astype(np.float32)
+        got = Q.qsac_adaptive_thresholds(list(s), eta, p)
+        want = [oracle.adaptive_tau(float(x), float(np.float32(eta)), float(np.float32(p))) for x in s]
+        assert np.allclose(got, want, rtol=0, atol=6e-8)
+        assert got[1] == pytest.approx(eta, abs=6e-8) and got[0] == pytest.approx(-1.0, abs=6e-8)
+    # the hand-derived fixture values
+    gold = os.path.join(ROOT, "tests", "golden", "eq345_thresholds.txt")
+    for line in open(gold):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            s_i, eta, p, want = [float(x) for x in line.split(";")[:4]]
+            assert Q.qsac_adaptive_thresholds([s_i], eta, p)[0] == pytest.approx(want, abs=1e-6)
+    for bad in (dict(importance=[1.5], eta=0.8, p=3), dict(importance=[0.5], eta=1.5, p=3),
+                dict(importance=[0.5], eta=0.8, p=0), dict(importance=[-0.1], eta=0.8, p=3)):
+        with pytest.raises(Q.QsacError):
+            Q.qsac_adaptive_thresholds(**bad)
+
+
+def test_reuse_difficulty_matches_the_oracle(lib, oracle):
+    tau, sim = [0.8, 0.5, -0.2], [0.9, 0.6, 0.95]
+    got = Q.qsac_reuse_difficulty(tau, sim, 0.1)
+    import numpy as np
+    f = lambda x: float(np.float32(x))
+    want = [oracle.reuse_difficulty(f(t), f(s), f(0.1)) for t, s in zip(tau, sim)]
+    assert np.allclose(got, want, atol=6e-8)
+    with pytest.raises(Q.QsacError):
+        Q.qsac_reuse_difficulty(tau, sim, 0.0)

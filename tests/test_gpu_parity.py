@@ -110,10 +110,27 @@ def test_attention_with_several_tiles_per_wave(H):
     run_chain(H, B=4, Hq=8, Hkv=2, N=40000, k=3000, k_max=3000, dtype="bf16", steps=5, tau=0.93, expect_both=False)
 
 
-@pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_SCORE_VALU])
-def test_large_n_path(H, flags):
-    """N above 131072 takes the grid-wide select (histogram fused into scoring, refine, mark, diff)."""
-    run_chain(H, B=1, Hq=8, Hkv=2, N=140001, k=700, k_max=700, dtype="bf16", steps=6, flags=flags, tau=0.93)
+@pytest.mark.parametrize("flags,N", [(0, 140001), (Q.QSAC_FLAG_SCORE_VALU, 140001), (0, 270001)])
+def test_large_n_path(H, flags, N):
+    """N above 65536 takes the grid-wide select (histogram fused into scoring, refine, mark, diff); above
+    262144 keys the diff holds 32 bitmap words per lane instead of 8."""
+    run_chain(H, B=1, Hq=8, Hkv=2, N=N, k=700, k_max=700, dtype="bf16", steps=6, flags=flags, tau=0.93)
+
+
+def test_adaptive_thresholds_drive_the_gate(H):
+    """Eq. (3)-(5): thresholds from synthetic KV-head importance scores (eta = 0.8, p = 3 as in the paper's
+    setup) feed the per-head tau input; the unimportant head reuses far more often than the important one."""
+    tau = Q.qsac_adaptive_thresholds([1.0, 0.97, 0.6, 0.0], 0.8, 3.0)
+    assert tau[0] == pytest.approx(0.8, abs=1e-6) and tau[3] == pytest.approx(-1.0, abs=1e-6) and tau[0] > tau[1] > tau[2] > tau[3]
+    sess, Kb, Ksb, Vsb = H.make_session(1, 8, 4, 3000, 128, "bf16", seed=9)
+    par = H.Parity(sess, "bf16", Kb, Ksb, Vsb)
+    chain = W.QueryChain(1, 8, 128, 0.9, 9)
+    reuse = np.zeros(4)
+    for t in range(24):
+        par.step(chain.next(), tau, 128, label=f"adaptive step {t}")
+        reuse += sess.reuse_flags.cpu().numpy().reshape(-1)
+    assert reuse[3] == 23 and reuse[0] < reuse[2] <= reuse[3]
+    sess.close()
 
 
 @pytest.mark.parametrize("N", [65536, 65537])
