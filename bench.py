@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--workload", default="llama3_8b_32k")
     ap.add_argument("--tau", type=float, default=None, help="override the workload's threshold")
     ap.add_argument("--flags", type=int, default=0, help="extra qsac_config.flags (e.g. 4 = ALU scoring)")
+    ap.add_argument("--resident", type=int, default=0,
+                    help="keep this many KV heads resident in HBM (Section 4.4), chosen by reuse difficulty")
     ap.add_argument("--side-stream", action="store_true",
                     help="give the library a second stream (attention of reused heads, or the fill kernel, runs on it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -107,14 +109,29 @@ def main():
         V_host = torch.empty(V_dev.shape, dtype=V_dev.dtype, pin_memory=True).copy_(V_dev)
     K_src = K_host if w.host_k else K_dev
     V_src = V_host if w.host_v else V_dev
+    q_all = make_queries(w, W, total)
+    V_res = res_slot = None
+    if a.resident:
+        # reuse difficulty D_i = tau_i - (s_hat_i - eps) from the adjacent-query cosines of the chain itself
+        # (the paper profiles s_hat offline on sample sequences); the hardest heads become resident
+        qf = q_all.double()
+        cos = (qf[1:] * qf[:-1]).sum(-1) / (qf[1:].norm(dim=-1) * qf[:-1].norm(dim=-1))     # [T-1,B,Hq]
+        cos = cos.reshape(total - 1, w.B, w.Hkv, w.G).clamp_min(1e-6)
+        s_hat = (w.G / (1.0 / cos).sum(-1)).mean(dim=(0, 1))                                 # Eq. (2), then mean
+        D = Q.qsac_reuse_difficulty([tau] * w.Hkv, s_hat.tolist(), 0.1)
+        hard = sorted(range(w.Hkv), key=lambda h: -D[h])[:a.resident]
+        res_slot = [-1] * w.Hkv
+        for i, h in enumerate(sorted(hard)):
+            res_slot[h] = i
+        V_res = torch.stack([V_dev[:, h] for h in sorted(hard)], dim=1).contiguous()
     if w.host_v:
-        V_dev = None  # the offload workloads keep V on the host only
-    q_dev = make_queries(w, W, total).cuda()
+        V_dev = None  # the offload workloads keep V on the host only (and in V_res for resident heads)
+    q_dev = q_all.cuda()
     torch.cuda.synchronize()
 
     def session(flags):
         return Q.Session(w.B, w.Hq, w.Hkv, w.N, w.k, w.dtype, K_dev, K_src, V_src, flags=flags | a.flags,
-                         side_stream=bool(a.side_stream))
+                         side_stream=bool(a.side_stream), V_res=V_res, res_slot=res_slot)
 
     # ---- timed run: K steps after W warmup steps, overlapped fill, no events inside
     sess = session(0)
@@ -149,7 +166,12 @@ def main():
                                    if a.side_stream else None)},
         "reuse_rate": reuse_rate, "slot_hit_rate": slot_hit_rate,
         "rows_filled_per_step": d["slot_misses"] / K_steps,
+        "rows_filled_from_host_per_step": ((d["slot_misses"] - d["resident_rows"]) / K_steps
+                                           if (w.host_k or w.host_v) else 0.0),
     }
+    if a.resident:
+        result["config"]["resident_kv_heads"] = sorted(hard)
+        result["config"]["reuse_difficulty"] = [round(x, 4) for x in D]
 
     # ---- stage timing (HIP events on the stream the kernels run on), same steps, fill not overlapped
     if not a.no_profile:

@@ -133,6 +133,13 @@ typedef struct {
   uint8_t *hit_mask;    /* DEVICE [B,Hkv,k]         1 where topk_idx[j] was cached before the step           */
   uint8_t *reuse_flags; /* DEVICE [B,Hkv]           1 where the gate reused the cached set                   */
   float *sim;           /* DEVICE f32 [B,Hq] or NULL  per-query-head CosSim                                   */
+  /* Resident caching (Section 4.4): KV heads that are hard to reuse keep their full KV in HBM, so their
+     misses never cross PCIe.  A head h with res_slot[h] >= 0 takes the K rows of its missing tokens from
+     K_dev and the V rows from V_res[:, res_slot[h]]; the others use K_src / V_src.  Results do not depend
+     on which heads are resident.  NULL res_slot = no resident heads. */
+  const void *V_res;         /* DEVICE e [B,n_res,N,D] or NULL  full V of the resident KV heads          */
+  const int8_t *res_slot;    /* HOST [n_kv_heads] or NULL       index in V_res, -1 = not resident         */
+  int32_t n_res;             /* resident KV heads, 1 <= n_res <= n_kv_heads when res_slot is given       */
 } qsac_step_args;
 
 /* Cumulative since init / reset, summed over pairs. */
@@ -142,7 +149,8 @@ typedef struct {
   uint64_t miss_heads;   /* pairs that took the miss branch             */
   uint64_t slot_hits;    /* rows of a fresh top-k that were cached      */
   uint64_t slot_misses;  /* rows filled from the fill sources           */
-  uint64_t reserved[3];
+  uint64_t resident_rows;/* of those, rows of resident heads (from HBM) */
+  uint64_t reserved[2];
 } qsac_stats;
 
 /* Workspace size for a configuration (pure host function; 0 if the configuration is invalid). */

@@ -45,12 +45,14 @@ class qsac_step_args(C.Structure):
     _fields_ = [("q", C.c_void_p), ("K_dev", C.c_void_p), ("K_src", C.c_void_p), ("V_src", C.c_void_p),
                 ("K_slots", C.c_void_p), ("V_slots", C.c_void_p), ("slot_idx", C.c_void_p), ("prev_q", C.c_void_p),
                 ("tau", C.POINTER(C.c_float)), ("n_tau", C.c_int32), ("k", C.c_int32), ("out", C.c_void_p),
-                ("topk_idx", C.c_void_p), ("hit_mask", C.c_void_p), ("reuse_flags", C.c_void_p), ("sim", C.c_void_p)]
+                ("topk_idx", C.c_void_p), ("hit_mask", C.c_void_p), ("reuse_flags", C.c_void_p), ("sim", C.c_void_p),
+                ("V_res", C.c_void_p), ("res_slot", C.POINTER(C.c_int8)), ("n_res", C.c_int32)]
 
 
 class qsac_stats(C.Structure):
     _fields_ = [("steps", C.c_uint64), ("reuse_heads", C.c_uint64), ("miss_heads", C.c_uint64),
-                ("slot_hits", C.c_uint64), ("slot_misses", C.c_uint64), ("reserved", C.c_uint64 * 3)]
+                ("slot_hits", C.c_uint64), ("slot_misses", C.c_uint64), ("resident_rows", C.c_uint64),
+                ("reserved", C.c_uint64 * 2)]
 
 
 _lib = None
@@ -133,7 +135,8 @@ def qsac_get_stats(ctx) -> dict:
     rc = load().qsac_get_stats(ctx, C.byref(st))
     if rc:
         raise QsacError(rc, "qsac_get_stats")
-    return {n: int(getattr(st, n)) for n in ("steps", "reuse_heads", "miss_heads", "slot_hits", "slot_misses")}
+    return {n: int(getattr(st, n)) for n in ("steps", "reuse_heads", "miss_heads", "slot_hits", "slot_misses",
+                                             "resident_rows")}
 
 
 def qsac_get_stage_ms(ctx):
@@ -203,7 +206,8 @@ class Session:
     """
 
     def __init__(self, B, Hq, Hkv, N, k_max, dtype: str, K_dev, K_src, V_src, flags=0, importance=None,
-                 side_stream=False):
+                 side_stream=False, V_res=None, res_slot=None):
+        """V_res [B,n_res,N,128] (device) and res_slot [Hkv] make the KV heads with res_slot >= 0 resident."""
         import torch
         from .workload import DTYPE_CODES, TORCH_DTYPES
         assert torch.cuda.is_available(), "QSAC needs a GPU: there is no CPU path"
@@ -213,6 +217,10 @@ class Session:
         P = B * Hkv
         self.B, self.Hq, self.Hkv, self.N, self.k_max, self.P = B, Hq, Hkv, N, k_max, P
         self.K_dev, self.K_src, self.V_src = K_dev, K_src, V_src
+        self.V_res, self.res_slot = V_res, (None if res_slot is None else [int(x) for x in res_slot])
+        if V_res is not None:
+            assert V_res.is_cuda and V_res.is_contiguous() and V_res.dtype == tdt and len(self.res_slot) == Hkv
+            assert V_res.shape == (B, V_res.shape[1], N, 128)
         for t in (K_dev, K_src, V_src):
             assert t.shape == (B, Hkv, N, 128) and t.dtype == tdt and t.is_contiguous()
         assert K_dev.is_cuda
@@ -259,6 +267,10 @@ class Session:
         a.prev_q, a.tau, a.n_tau, a.k = self.prev_q.data_ptr(), C.cast(tau_arr, C.POINTER(C.c_float)), len(taus), k
         a.out, a.topk_idx, a.hit_mask = self.out.data_ptr(), self.topk_idx.data_ptr(), self.hit_mask.data_ptr()
         a.reuse_flags, a.sim = self.reuse_flags.data_ptr(), self.sim.data_ptr()
+        if self.V_res is not None:
+            rs = (C.c_int8 * self.Hkv)(*self.res_slot)
+            a._keep_rs = rs
+            a.V_res, a.res_slot, a.n_res = self.V_res.data_ptr(), C.cast(rs, C.POINTER(C.c_int8)), self.V_res.shape[1]
         self._last_q = q  # keep the tensor alive until the stream has consumed it
         qsac_step(self.ctx, a)
 

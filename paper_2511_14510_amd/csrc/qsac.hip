@@ -170,20 +170,19 @@ void launch_score(const qsac_ctx* c, const qsac_step_args* a, u32* keys, u32* hi
 }
 
 template <int DT, int G>
-void launch_attn(const qsac_ctx* c, const qsac_step_args* a, hipStream_t stream, dim3 grid, const int* fetch_tok,
-                 const int* miss_count, float* part_ml, float* part_acc, int rows, int n_splits, int which) {
+void launch_attn(const qsac_ctx* c, const qsac_step_args* a, hipStream_t stream, dim3 grid, const FillSrc& src,
+                 const int* fetch_tok, const int* miss_count, float* part_ml, float* part_acc, int rows, int n_splits,
+                 int which) {
   auto q = static_cast<const uint16_t*>(a->q);
   auto Ks = static_cast<v4u*>(a->K_slots);
   auto Vs = static_cast<v4u*>(a->V_slots);
-  auto Kf = static_cast<const v4u*>(a->K_src);
-  auto Vf = static_cast<const v4u*>(a->V_src);
   if (c->fill_kernel)
     qsac_attn_kernel<DT, G, false><<<grid, 256, 0, stream>>>(
-        q, Ks, Vs, Kf, Vf, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads,
+        q, Ks, Vs, src, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads,
         c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits, which);
   else
     qsac_attn_kernel<DT, G, true><<<grid, 256, 0, stream>>>(
-        q, Ks, Vs, Kf, Vf, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads,
+        q, Ks, Vs, src, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads,
         c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits, which);
 }
 
@@ -320,6 +319,13 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   const void* al[] = {a->q, a->K_dev, a->K_src, a->V_src, a->K_slots, a->V_slots, a->slot_idx, a->prev_q, a->out, a->topk_idx};
   for (const void* ptr : al)
     if (!aligned16(ptr)) return QSAC_EALIGN;
+  if (a->res_slot) {
+    if (!a->V_res) return QSAC_ENULL;
+    if (a->n_res < 1 || a->n_res > c->cfg.n_kv_heads) return QSAC_ERANGE;
+    if (!aligned16(a->V_res)) return QSAC_EALIGN;
+    for (int h = 0; h < c->cfg.n_kv_heads; ++h)
+      if (a->res_slot[h] < -1 || a->res_slot[h] >= a->n_res) return QSAC_ERANGE;
+  }
   c->k_bound = a->k;
   c->steps += 1;
   if (c->dry) return QSAC_OK;
@@ -358,6 +364,13 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
 
   TauArg tau;
   for (int h = 0; h < Hkv; ++h) tau.v[h] = a->tau[a->n_tau == 1 ? 0 : h];
+  FillSrc src;
+  src.K_src = static_cast<const v4u*>(a->K_src);
+  src.V_src = static_cast<const v4u*>(a->V_src);
+  src.K_res = static_cast<const v4u*>(a->K_dev);
+  src.V_res = static_cast<const v4u*>(a->V_res);
+  src.n_res = a->res_slot ? a->n_res : 0;
+  for (int h = 0; h < 64; ++h) src.slot[h] = (a->res_slot && h < Hkv) ? a->res_slot[h] : -1;
 
   // 1. gate (+ label update on a miss)
   mark(0);
@@ -374,12 +387,11 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
   dim3 attn_grid((unsigned)n_splits, (unsigned)P);
   auto fill_on = [&](hipStream_t s) {
-    qsac_fill_kernel<<<fill_grid, 256, 0, s>>>(miss_count, miss_slot, miss_tok, static_cast<const v4u*>(a->K_src),
-                                               static_cast<const v4u*>(a->V_src), static_cast<v4u*>(a->K_slots),
-                                               static_cast<v4u*>(a->V_slots), N, k_max);
+    qsac_fill_kernel<<<fill_grid, 256, 0, s>>>(miss_count, miss_slot, miss_tok, src, static_cast<v4u*>(a->K_slots),
+                                               static_cast<v4u*>(a->V_slots), Hkv, N, k_max);
   };
   auto attend = [&](hipStream_t s, int which) {
-    QSAC_DISPATCH(launch_attn, c, a, s, attn_grid, fetch_tok, miss_count, part_ml, part_acc, rows, n_splits, which);
+    QSAC_DISPATCH(launch_attn, c, a, s, attn_grid, src, fetch_tok, miss_count, part_ml, part_acc, rows, n_splits, which);
   };
   auto combine = [&]() {
     if (n_splits > 1)
@@ -411,8 +423,8 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
 #define QSAC_SELECT(VPT)                                                                                          \
   qsac_select_small_kernel<VPT><<<P, kDiffThreads, lds, sm>>>(a->reuse_flags, keys, valid, a->slot_idx, set_sorted, \
                                                              a->topk_idx, a->hit_mask, miss_count, miss_slot,      \
-                                                             miss_tok, fetch_tok, stats, N, L.n_pad, k, k_max,     \
-                                                             bm_words)
+                                                             miss_tok, fetch_tok, stats, src, Hkv, N, L.n_pad, k,  \
+                                                             k_max, bm_words)
     if (nvec <= 2 * kDiffThreads) QSAC_SELECT(2);
     else if (nvec <= 4 * kDiffThreads) QSAC_SELECT(4);
     else if (nvec <= 8 * kDiffThreads) QSAC_SELECT(8);
@@ -428,7 +440,7 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
 #define QSAC_DIFF(WPL)                                                                                             \
   qsac_diff_kernel<WPL><<<P, kDiffThreads, 0, sm>>>(a->reuse_flags, valid, bm_new, bm_eq, bm_old, sel_r, a->slot_idx, \
                                                    set_sorted, a->topk_idx, a->hit_mask, miss_count, miss_slot,     \
-                                                   miss_tok, fetch_tok, stats, L.words, k, k_max)
+                                                   miss_tok, fetch_tok, stats, src, Hkv, L.words, k, k_max)
     if (L.words <= 8 * kDiffThreads) QSAC_DIFF(8);
     else QSAC_DIFF(32);
 #undef QSAC_DIFF
@@ -474,6 +486,7 @@ int qsac_get_stats(qsac_ctx* c, qsac_stats* out) {
   out->miss_heads = dev[2];
   out->slot_hits = dev[3];
   out->slot_misses = dev[4];
+  out->resident_rows = dev[5];
   return QSAC_OK;
 }
 

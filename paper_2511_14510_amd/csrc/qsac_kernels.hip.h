@@ -50,6 +50,31 @@ struct TauArg {
   float v[64];  // per KV head
 };
 
+// Where the K / V rows of a pair's missing tokens come from.  A resident KV head (Section 4.4 of
+// the paper: heads that are hard to reuse keep their full KV in HBM) takes K rows from the HBM
+// copy of K that scoring reads and V rows from the resident V tensor [B, n_res, N, D]; the others
+// take both from the fill sources (HBM or host-mapped pinned memory), [B, Hkv, N, D].
+struct FillSrc {
+  const v4u* K_src;
+  const v4u* V_src;
+  const v4u* K_res;
+  const v4u* V_res;
+  int n_res;
+  signed char slot[64];  // per KV head: index in V_res, -1 if not resident
+};
+__device__ __forceinline__ void fill_rows_of(const FillSrc& f, int p, int Hkv, int64_t N, const v4u*& Ks,
+                                             const v4u*& Vs) {
+  const int b = p / Hkv, h = p % Hkv;
+  const int rs = f.slot[h];
+  if (rs >= 0) {
+    Ks = f.K_res + (size_t)p * (size_t)N * kRowU4;
+    Vs = f.V_res + ((size_t)b * f.n_res + rs) * (size_t)N * kRowU4;
+  } else {
+    Ks = f.K_src + (size_t)p * (size_t)N * kRowU4;
+    Vs = f.V_src + (size_t)p * (size_t)N * kRowU4;
+  }
+}
+
 // ---------------------------------------------------------------- small helpers
 
 __device__ __forceinline__ u32 fbits(float f) { return __builtin_bit_cast(u32, f); }
@@ -558,7 +583,7 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
                                             int* __restrict__ tk, uint8_t* __restrict__ hm, int* __restrict__ ms,
                                             int* __restrict__ mt, int* __restrict__ ft,
                                             int* __restrict__ miss_count_p, u32* __restrict__ valid_p,
-                                            u64* __restrict__ stats, int* s_wave) {
+                                            u64* __restrict__ stats, bool resident, int* s_wave) {
   constexpr int NW = NT / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // Wave w owns the contiguous words [wb, we); lane l takes words wb + l, wb + l + 64, ... (at most
@@ -694,6 +719,7 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
     *valid_p = 1;
     atomicAdd(&stats[3], (u64)(k - m));
     atomicAdd(&stats[4], (u64)m);
+    if (resident) atomicAdd(&stats[5], (u64)m);
   }
 }
 
@@ -705,8 +731,8 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
     const u32* __restrict__ bm_eq, u32* __restrict__ bm_old, const int* __restrict__ sel_r,
     int* __restrict__ slot_idx, int* __restrict__ set_sorted, int* __restrict__ topk_idx,
     uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count, int* __restrict__ miss_slot,
-    int* __restrict__ miss_tok, int* __restrict__ fetch_tok, u64* __restrict__ stats, int words, int k,
-    int k_max) {
+    int* __restrict__ miss_tok, int* __restrict__ fetch_tok, u64* __restrict__ stats, FillSrc src, int Hkv,
+    int words, int k, int k_max) {
   const int p = blockIdx.x;
   if (reuse_flags[p]) return;
   __shared__ int s_wave[17];
@@ -714,7 +740,8 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
                             valid[p] != 0, sel_r[p], words, k, slot_idx + (size_t)p * k_max,
                             set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
                             miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max,
-                            fetch_tok + (size_t)p * k_max, miss_count + p, valid + p, stats, s_wave);
+                            fetch_tok + (size_t)p * k_max, miss_count + p, valid + p, stats,
+                            src.slot[p % Hkv] >= 0, s_wave);
 }
 
 // OR over aligned groups of 8 lanes (DPP: xor 1, xor 2, then mirror within each half row).
@@ -735,8 +762,8 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
     const uint8_t* __restrict__ reuse_flags, const u32* __restrict__ keys, u32* __restrict__ valid,
     int* __restrict__ slot_idx, int* __restrict__ set_sorted, int* __restrict__ topk_idx,
     uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count, int* __restrict__ miss_slot,
-    int* __restrict__ miss_tok, int* __restrict__ fetch_tok, u64* __restrict__ stats, int64_t N, int64_t n_pad,
-    int k, int k_max, int bm_words) {
+    int* __restrict__ miss_tok, int* __restrict__ fetch_tok, u64* __restrict__ stats, FillSrc src, int Hkv,
+    int64_t N, int64_t n_pad, int k, int k_max, int bm_words) {
   const int p = blockIdx.x;
   if (reuse_flags[p]) return;
   constexpr int NT = kDiffThreads;
@@ -816,7 +843,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
   diff_phases<NT, 2>(s_new, s_eq, s_old, valid[p] != 0, need, words, k, slot_idx + (size_t)p * k_max,
                   set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
                   miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max, fetch_tok + (size_t)p * k_max,
-                  miss_count + p, valid + p, stats, s_wave);
+                  miss_count + p, valid + p, stats, src.slot[p % Hkv] >= 0, s_wave);
 }
 
 // ---------------------------------------------------------------- fill
@@ -828,9 +855,9 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
 __global__ __launch_bounds__(256) void qsac_fill_kernel(const int* __restrict__ miss_count,
                                                         const int* __restrict__ miss_slot,
                                                         const int* __restrict__ miss_tok,
-                                                        const v4u* __restrict__ K_src, const v4u* __restrict__ V_src,
-                                                        v4u* __restrict__ K_slots, v4u* __restrict__ V_slots,
-                                                        int64_t N, int k_max) {
+                                                        FillSrc src, v4u* __restrict__ K_slots,
+                                                        v4u* __restrict__ V_slots, int Hkv, int64_t N,
+                                                        int k_max) {
   const int p = blockIdx.y;
   const int m = miss_count[p];
   const int e0 = blockIdx.x * kFillRows;
@@ -838,8 +865,8 @@ __global__ __launch_bounds__(256) void qsac_fill_kernel(const int* __restrict__ 
   const int c = threadIdx.x & 15, grp = threadIdx.x >> 4;
   const int* ms = miss_slot + (size_t)p * k_max;
   const int* mt = miss_tok + (size_t)p * k_max;
-  const v4u* Ks = K_src + (size_t)p * (size_t)N * kRowU4;
-  const v4u* Vs = V_src + (size_t)p * (size_t)N * kRowU4;
+  const v4u *Ks, *Vs;
+  fill_rows_of(src, p, Hkv, N, Ks, Vs);
   v4u* Kd = K_slots + (size_t)p * k_max * kRowU4;
   v4u* Vd = V_slots + (size_t)p * k_max * kRowU4;
   int slot[4];
@@ -901,8 +928,8 @@ __device__ __forceinline__ float row16_max(float v) {
 
 template <int DT, int G, bool FETCH>
 __global__ __launch_bounds__(256) void qsac_attn_kernel(
-    const uint16_t* __restrict__ q, v4u* __restrict__ K_slots, v4u* __restrict__ V_slots,
-    const v4u* __restrict__ K_src, const v4u* __restrict__ V_src, const int* __restrict__ fetch_tok,
+    const uint16_t* __restrict__ q, v4u* __restrict__ K_slots, v4u* __restrict__ V_slots, FillSrc src,
+    const int* __restrict__ fetch_tok,
     const int* __restrict__ miss_count, const uint8_t* __restrict__ reuse_flags, float* __restrict__ part_ml,
     float* __restrict__ part_acc, float* __restrict__ out, int Hq, int Hkv, int64_t N, int k, int k_max, int rows,
     int n_splits, int max_splits, int which) {
@@ -923,8 +950,8 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
   for (int j = 0; j < 4; ++j) qa[j] = (m < G) ? qg[m * kRowU4 + quarter * 4 + j] : v4u{0, 0, 0, 0};
   v4u* Kp = K_slots + (size_t)p * k_max * kRowU4;
   v4u* Vp = V_slots + (size_t)p * k_max * kRowU4;
-  const v4u* Ks = K_src + (size_t)p * (size_t)N * kRowU4;
-  const v4u* Vs = V_src + (size_t)p * (size_t)N * kRowU4;
+  const v4u *Ks, *Vs;
+  fill_rows_of(src, p, Hkv, N, Ks, Vs);
   const int* ft = fetch_tok + (size_t)p * k_max;
   const bool fetch = FETCH && miss_count[p] > 0;  // uniform over the workgroup
 

@@ -96,7 +96,7 @@ def test_workspace_checks_without_dry_run(lib):
 def _args(**over):
     a = Q.qsac_step_args()
     for f, _ in Q.qsac_step_args._fields_:
-        if f not in ("tau", "n_tau", "k"):
+        if f not in ("tau", "n_tau", "k", "V_res", "res_slot", "n_res"):
             setattr(a, f, 0x10000)
     tau = (C.c_float * 2)(0.9, 0.8)
     a._keep = tau
@@ -125,6 +125,14 @@ def test_step_validation_on_a_dry_run_context(lib):
     assert step(_args(k=0)) == Q.QSAC_ERANGE
     assert step(_args(k=257)) == Q.QSAC_ERANGE
     assert step(_args(q=0x10008)) == Q.QSAC_EALIGN
+    rs = (C.c_int8 * 2)(0, -1)
+    rsp = C.cast(rs, C.POINTER(C.c_int8))
+    assert step(_args(res_slot=rsp, n_res=1)) == Q.QSAC_ENULL      # resident heads without a resident V
+    assert step(_args(res_slot=rsp, n_res=1, V_res=0x20000)) == Q.QSAC_OK
+    assert step(_args(res_slot=rsp, n_res=0, V_res=0x20000)) == Q.QSAC_ERANGE
+    assert step(_args(res_slot=rsp, n_res=3, V_res=0x20000)) == Q.QSAC_ERANGE
+    bad = (C.c_int8 * 2)(1, -1)
+    assert step(_args(res_slot=C.cast(bad, C.POINTER(C.c_int8)), n_res=1, V_res=0x20000)) == Q.QSAC_ERANGE
     assert step(_args(k=128)) == Q.QSAC_ESTATE                     # k changed without a reset
     Q.qsac_reset(ctx)
     assert step(_args(k=128)) == Q.QSAC_OK

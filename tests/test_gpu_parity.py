@@ -92,6 +92,30 @@ def test_fill_from_pinned_host_memory(H, flags):
               flags=flags)
 
 
+@pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_FILL_KERNEL])
+def test_resident_heads_never_touch_their_host_rows(H, flags):
+    """Resident caching (Section 4.4): KV heads 1 and 3 keep their full V in HBM (V_res) and take K rows from
+    K_dev.  Their regions of the host-side fill sources are overwritten with other values, so any read from
+    there would show up as wrong slot rows or outputs; the results must equal those of the oracle on the true K, V."""
+    B, Hq, Hkv, N, k = 2, 8, 4, 5000, 300
+    K, V = W.make_kv(B, Hkv, N, 128, "bf16", 31)
+    res_slot = [-1, 0, -1, 1]
+    K_bad, V_bad = K.clone(), V.clone()
+    for h in (1, 3):
+        K_bad[:, h] = 7.0
+        V_bad[:, h] = -3.0
+    V_res = torch.stack([V[:, 1], V[:, 3]], dim=1).contiguous().cuda()
+    sess = Q.Session(B, Hq, Hkv, N, k, "bf16", K.cuda(), K_bad.pin_memory(), V_bad.pin_memory(), flags=flags,
+                     V_res=V_res, res_slot=res_slot, side_stream=bool(flags))
+    par = H.Parity(sess, "bf16", W.bits(K), W.bits(K), W.bits(V))
+    chain = W.QueryChain(B, Hq, 128, 0.95, 31)
+    for t in range(10):
+        par.step(chain.next(), 0.9, k, label=f"resident step {t}")
+    st = sess.stats()
+    assert par.n_reuse > 0 and 0 < st["resident_rows"] < st["slot_misses"]
+    sess.close()
+
+
 def test_per_head_tau_and_importance(H):
     imp = [0.2, 1.0, 3.0, 0.7, 1.0, 1.0, 0.1, 2.5]
     par = run_chain(H, B=2, Hq=8, Hkv=2, N=2000, k=100, k_max=100, dtype="bf16", steps=16, tau=[0.95, 0.8],
