@@ -31,6 +31,8 @@ typedef unsigned long long u64;
 constexpr int kD = 128;            // head_dim
 constexpr int kRowU4 = 16;         // 16-byte chunks per 256-byte row
 constexpr int kBins = 2048;        // bins per radix level (level 2 uses the first 1024)
+constexpr int kHistCopies = 4;     // one-workgroup select: lane l counts into copy l % 4 (fewer same-address conflicts)
+constexpr int kHistPitch = kBins + 16;  // words between copies: the same bin of different copies sits in different banks
 constexpr int kScoreRowsSmall = 256;   // keys per workgroup of the scoring kernel (small-N path)
 constexpr int kScoreRowsLarge = 1024;  // ... when the level-0 histogram is fused in (large-N path)
 constexpr int kSmallMaxN = 65536;      // largest N the one-workgroup select takes: its keys fit in the registers of 1024 threads
@@ -183,10 +185,33 @@ __device__ __forceinline__ int wave_totals_exclusive(int wave_value, int* s_wave
   return base;
 }
 
+// The same for two values per wave at once.
+template <int NW>
+__device__ __forceinline__ void wave_totals_exclusive2(int va, int vb, int* s_wave2 /*[2*NW]*/, int* base_a,
+                                                       int* base_b) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) {
+    s_wave2[wave] = va;
+    s_wave2[NW + wave] = vb;
+  }
+  __syncthreads();
+  int ba = 0, bb = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    if (w < wave) {
+      ba += s_wave2[w];
+      bb += s_wave2[NW + w];
+    }
+  }
+  *base_a = ba;
+  *base_b = bb;
+}
+
 // Among bins [0, nbins) of `hist`, finds the bin b with  count(bins > b) < need <= count(bins >= b).
 // Returns b; *above = count(bins > b).  NT threads (nbins is a multiple of NT, at most 8 bins per
-// thread); contains barriers.
-template <int NT>
+// thread); the histogram may be split over COPIES copies kHistPitch words apart; contains barriers.
+template <int NT, int COPIES = 1>
 __device__ __forceinline__ int find_bin(const u32* hist, int nbins, int need, int* above, int* s_wave,
                                         int* s_res) {
   const int per = nbins / NT;
@@ -196,7 +221,11 @@ __device__ __forceinline__ int find_bin(const u32* hist, int nbins, int need, in
   int local = 0;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    c[i] = (i < per) ? (int)hist[hi - i] : 0;
+    c[i] = 0;
+    if (i < per) {
+#pragma unroll
+      for (int cp = 0; cp < COPIES; ++cp) c[i] += (int)hist[cp * kHistPitch + hi - i];
+    }
     local += c[i];
   }
   if (threadIdx.x == 0) {
@@ -592,6 +621,17 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
   const int wpw = ((words + NW - 1) / NW + 63) & ~63;
   const int wb = min(wave * wpw, words), we = min(wb + wpw, words);
   const int rounds = wpw >> 6;  // <= WPL, uniform over the workgroup
+  // thread t owns the contiguous slots [j0, j1); up to four of their tokens are requested now and
+  // kept in registers for B and D (with more slots per thread they are re-read where needed)
+  const int spt = (k + NT - 1) / NT;
+  const int j0 = min(tid * spt, k), j1 = min(j0 + spt, k);
+  const bool slots_in_regs = spt <= 4;  // uniform
+  int mytok[4] = {0, 0, 0, 0};
+  if (was_valid && slots_in_regs) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (j0 + i < j1) mytok[i] = sl[j0 + i];
+  }
   for (int j = tid; j < k; j += NT) ft[j] = -1;  // slots that keep their row; E names the others
   int total;
   // A
@@ -634,11 +674,18 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
     }
   }
   // B
-  if (was_valid)
-    for (int j = tid; j < k; j += NT) {
-      const int tok = sl[j];
-      atomicOr(&old[tok >> 5], 1u << (tok & 31));
+  if (was_valid) {
+    if (slots_in_regs) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (j0 + i < j1) atomicOr(&old[mytok[i] >> 5], 1u << (mytok[i] & 31));
+    } else {
+      for (int j = j0; j < j1; ++j) {
+        const int tok = sl[j];
+        atomicOr(&old[tok >> 5], 1u << (tok & 31));
+      }
     }
+  }
   __syncthreads();
   // C
   u32 av[WPL], ov[WPL];
@@ -654,8 +701,8 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
   }
   cn = __shfl(wave_inclusive_scan(cn), 63);
   cm = __shfl(wave_inclusive_scan(cm), 63);
-  int runn = wave_totals_exclusive<NW>(cn, s_wave, &total);
-  int runm = wave_totals_exclusive<NW>(cm, s_wave, &total);
+  int runn, runm;
+  wave_totals_exclusive2<NW>(cn, cm, s_wave, &runn, &runm);
 #pragma unroll
   for (int u = 0; u < WPL; ++u) {
     if (u < rounds) {
@@ -686,26 +733,40 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
     }
   }
   // D
-  const int spt = (k + NT - 1) / NT;
-  const int j0 = min(tid * spt, k), j1 = min(j0 + spt, k);
+  bool evict[4] = {false, false, false, false};
   int ce = 0;
-  for (int j = j0; j < j1; ++j) {
-    bool ev = true;
-    if (was_valid) {
-      const int tok = sl[j];
-      ev = !((nw[tok >> 5] >> (tok & 31)) & 1u);
+  if (slots_in_regs) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (j0 + i < j1) {
+        evict[i] = !was_valid || !((nw[mytok[i] >> 5] >> (mytok[i] & 31)) & 1u);
+        ce += evict[i];
+      }
+  } else {
+    for (int j = j0; j < j1; ++j) {
+      bool e = true;
+      if (was_valid) {
+        const int tok = sl[j];
+        e = !((nw[tok >> 5] >> (tok & 31)) & 1u);
+      }
+      ce += e;
     }
-    ce += ev;
   }
   int je = block_exclusive_scan<NT / 64>(ce, s_wave, &total);
   const int m = total;
-  for (int j = j0; j < j1; ++j) {
-    bool ev = true;
-    if (was_valid) {
-      const int tok = sl[j];
-      ev = !((nw[tok >> 5] >> (tok & 31)) & 1u);
+  if (slots_in_regs) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (evict[i]) ms[je++] = j0 + i;
+  } else {
+    for (int j = j0; j < j1; ++j) {
+      bool e = true;
+      if (was_valid) {
+        const int tok = sl[j];
+        e = !((nw[tok >> 5] >> (tok & 31)) & 1u);
+      }
+      if (e) ms[je++] = j;
     }
-    if (ev) ms[je++] = j;
   }
   __syncthreads();
   // E
@@ -735,7 +796,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
     int words, int k, int k_max) {
   const int p = blockIdx.x;
   if (reuse_flags[p]) return;
-  __shared__ int s_wave[17];
+  __shared__ int s_wave[32];
   diff_phases<kDiffThreads, WPL>(bm_new + (size_t)p * words, bm_eq + (size_t)p * words, bm_old + (size_t)p * words,
                             valid[p] != 0, sel_r[p], words, k, slot_idx + (size_t)p * k_max,
                             set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
@@ -769,18 +830,22 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
   constexpr int NT = kDiffThreads;
   constexpr int NV = VPT;
   extern __shared__ u32 s_dyn[];
-  __shared__ u32 s_hist[kBins];
-  __shared__ int s_wave[17];
+  __shared__ u32 s_hist[kHistCopies * kHistPitch];
+  __shared__ int s_wave[32];
   __shared__ int s_res[2];
   u32* s_new = s_dyn;
   u32* s_eq = s_dyn + bm_words;
   u32* s_old = s_dyn + 2 * bm_words;
   const int tid = threadIdx.x;
+  u32* my_hist = s_hist + (tid & (kHistCopies - 1)) * kHistPitch;
   const v4u* kp4 = reinterpret_cast<const v4u*>(keys + (size_t)p * n_pad);
   const int n = (int)N;
   const int nvec = (n + 3) >> 2;  // n_pad is a multiple of 8192, so whole vectors can be read
   const int words = (n + 31) >> 5;
 
+  // Keys at and past N read as 0 (the scoring kernel writes 0 there, vectors past the end are
+  // zeroed here).  0 is below the key of every finite score, so it never reaches the k-th key's
+  // bin, never matches a prefix and never compares above or equal to T: no range checks below.
   v4u kreg[NV];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
@@ -797,40 +862,37 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
     const int shift = level == 1 ? 21 : 10;  // from level 1 on, key >> shift must equal prefix
     const int sub = level == 0 ? 21 : (level == 1 ? 10 : 0);
     const u32 mask = level == 2 ? 0x3ffu : 0x7ffu;
-    for (int i = tid; i < kBins; i += NT) s_hist[i] = 0;
+    for (int i = tid; i < kHistCopies * kHistPitch; i += NT) s_hist[i] = 0;
     __syncthreads();
-    auto count = [&](const v4u kk, const int v) {
-      const int e = v * 4;
+    auto count = [&](const v4u kk) {
       const u32 ks[4] = {kk.x, kk.y, kk.z, kk.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const bool match = level == 0 || (ks[i] >> shift) == prefix;
-        if (e + i < n && match) atomicAdd(&s_hist[(ks[i] >> sub) & mask], 1u);
+        if (match) atomicAdd(&my_hist[(ks[i] >> sub) & mask], 1u);
       }
     };
 #pragma unroll
-    for (int i = 0; i < NV; ++i) count(kreg[i], tid + i * NT);
+    for (int i = 0; i < NV; ++i) count(kreg[i]);
     __syncthreads();
     const int nb = level == 2 ? 1024 : kBins;
-    const u32 b = (u32)find_bin<NT>(s_hist, nb, need, &above, s_wave, s_res);
+    const u32 b = (u32)find_bin<NT, kHistCopies>(s_hist, nb, need, &above, s_wave, s_res);
     need -= above;
     prefix = level == 0 ? b : (prefix << (level == 1 ? 11 : 10)) | b;
   }
   const u32 T = prefix;  // the k-th largest key; `need` of the keys equal to it belong to the set
   // bitmaps: a key vector is a nibble; 8 neighbouring lanes hold the 8 nibbles of one word
   auto nibbles = [&](const v4u kk, const int v) {
-    const int e = v * 4;
     const u32 ks[4] = {kk.x, kk.y, kk.z, kk.w};
     u32 g = 0, q = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const bool in = e + i < n;
-      g |= (u32)(in && ks[i] > T) << i;
-      q |= (u32)(in && ks[i] == T) << i;
+      g |= (u32)(ks[i] > T) << i;
+      q |= (u32)(ks[i] == T) << i;
     }
     const int sh = (v & 7) * 4;
     g = or8(g << sh);
-    q = or8(q << sh);
+    if (__ballot(q != 0)) q = or8(q << sh);  // uniform over the wave; keys equal to T are rare
     if ((v & 7) == 0 && (v >> 3) < words) {
       s_new[v >> 3] = g;
       s_eq[v >> 3] = q;
