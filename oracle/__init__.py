@@ -34,6 +34,11 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+class _Ext(C.Structure):
+    _fields_ = [("n_sink", C.c_int32), ("n_recent", C.c_int32), ("n_app", C.c_int32), ("app_cap", C.c_int32),
+                ("K_app", C.c_void_p), ("V_app", C.c_void_p)]
+
+
 class _Dims(C.Structure):
     _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
                 ("N", C.c_int64), ("k", C.c_int32), ("k_max", C.c_int32), ("dtype", C.c_int32)]
@@ -65,7 +70,9 @@ def lib():
         L.qo_diff.argtypes = [C.c_int, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_void_p]
         L.qo_step.restype = C.c_int
-        L.qo_step.argtypes = [C.POINTER(_Dims)] + [C.c_void_p] * 22
+        L.qo_step.argtypes = [C.POINTER(_Dims)] + [C.c_void_p] * 22 + [C.POINTER(_Ext)]
+        L.qo_attention_hybrid.restype = None
+        L.qo_attention_hybrid.argtypes = [C.c_void_p] * 3 + [C.c_int] + [C.c_void_p] * 2 + [C.c_int] * 3 + [C.c_void_p] * 2
         L.qo_num_threads.restype = C.c_int
         L.qo_set_num_threads.argtypes = [C.c_int]
         _lib = L
@@ -148,6 +155,18 @@ def attention(q, Kc, Vc, dtype: int):
     return out, w
 
 
+def attention_hybrid(q, Kc, Vc, Ka, Va, dtype: int):
+    """Attention over the cached rows followed by the appended rows (Section 6.2); returns (out, weights)."""
+    q, Kc, Vc, Ka, Va = _u16(q), _u16(Kc), _u16(Vc), _u16(Ka), _u16(Va)
+    k, D = Kc.shape
+    na = Ka.shape[0]
+    assert q.shape == (D,) and Vc.shape == (k, D) and Ka.shape == (na, D) and Va.shape == (na, D)
+    out = np.empty(D, dtype=np.float64)
+    w = np.empty(k + na, dtype=np.float64)
+    lib().qo_attention_hybrid(_p(q), _p(Kc), _p(Vc), k, _p(Ka), _p(Va), na, D, dtype, _p(out), _p(w))
+    return out, w
+
+
 def diff(valid: bool, N: int, slot_idx, topk_idx):
     """Slot diff of Algorithm 1's transfer step.  Returns (slot_idx', hit_mask, miss_slot, miss_tok)."""
     sl = np.array(slot_idx, dtype=np.int32, copy=True)
@@ -197,11 +216,15 @@ class StepResult:
 
 
 def step(state: State, q, K, K_src, V_src, tau, k: int, dtype: int, importance=None,
-         want_scores=False, want_weights=False, pair_mask=None) -> StepResult:
+         want_scores=False, want_weights=False, pair_mask=None, n_sink=0, n_recent=0, K_app=None, V_app=None,
+         n_app=0) -> StepResult:
     """One iteration of Algorithm 1 for every pair; ``state`` is updated in place.
 
     q [B,Hq,D], K/K_src/V_src [B,Hkv,N,D] as uint16 bit patterns; tau scalar or [Hkv].
     Pairs not marked in ``pair_mask`` are untouched (their outputs are undefined).
+    ``n_sink`` / ``n_recent``: the first / last tokens of the context that every retrieved set contains
+    (Section 7.1).  ``K_app`` / ``V_app`` [B,Hkv,cap,D] with ``n_app`` valid rows: the append-only buffer, attended
+    in full next to the cached rows (Section 6.2).
     """
     q = _u16(q)
     B, Hq, D = q.shape
@@ -225,13 +248,20 @@ def step(state: State, q, K, K_src, V_src, tau, k: int, dtype: int, importance=N
     kth = np.full(P, np.nan, np.float64)
     nf = np.zeros(P, np.int32)
     sc = np.empty((P, N), np.float64) if want_scores else None
-    wt = np.zeros((B, Hq, k), np.float64) if want_weights else None
+    wt = np.zeros((B, Hq, k + n_app), np.float64) if want_weights else None
+    assert n_sink >= 0 and n_recent >= 0 and n_sink + n_recent <= k
+    ext = _Ext(n_sink, n_recent, n_app, 0, None, None)
+    if n_app:
+        K_app, V_app = _u16(K_app), _u16(V_app)
+        cap = K_app.shape[2]
+        assert K_app.shape == (B, Hkv, cap, D) and V_app.shape == K_app.shape and 0 < n_app <= cap
+        ext.app_cap, ext.K_app, ext.V_app = cap, K_app.ctypes.data, V_app.ctypes.data
     pm = None if pair_mask is None else np.ascontiguousarray(pair_mask, dtype=np.uint8)
     dm = _Dims(B, Hq, Hkv, D, N, k, k_max, dtype)
     rc = lib().qo_step(C.byref(dm), _p(q), _p(K), _p(K_src), _p(V_src), _p(state.valid),
                        _p(state.prev_q), _p(state.slot_idx), _p(state.K_slots), _p(state.V_slots),
                        _p(tau_a), _p(imp), _p(out), _p(tk), _p(hm), _p(rf), _p(sim), _p(sa), _p(kth),
-                       _p(sc), _p(wt), _p(nf), _p(pm))
+                       _p(sc), _p(wt), _p(nf), _p(pm), C.byref(ext))
     if rc:
         raise ValueError(f"qo_step failed ({rc}): malformed cache state")
     return StepResult(out, tk, hm, rf, sim, sa, kth, nf, sc, wt)

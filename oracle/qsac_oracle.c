@@ -32,7 +32,13 @@
  *   - on a miss the cache ends up holding exactly Gather(K, V, index) as in
  *     Algorithm 1; rows already cached stay in their slots, the i-th slot
  *     (ascending) whose token left the set receives the i-th (ascending)
- *     token that entered it.
+ *     token that entered it;
+ *   - sink and recent tokens (Section 7.1: kept in the cache persistently): the
+ *     first n_sink and the last n_recent of the N context tokens rank above
+ *     every other token (score +infinity) in every retrieval;
+ *   - append-only buffer (Sections 6.1, 6.2): the KV of tokens generated during
+ *     decoding sit in a GPU buffer of which n_app rows are valid at a step; the
+ *     attention runs over the k cached rows and all n_app appended rows.
  *
  * Parity pins (tests/test_oracle_*.py) cover every function below; no
  * function here is "parity unpinned".
@@ -235,6 +241,35 @@ done:
   return rc;
 }
 
+/* ---- hybrid attention: cached rows plus the append-only buffer (Section 6.2) ---- */
+
+/* softmax over the k cached rows followed by the n_app appended rows; w_out (optional) has k + n_app entries. */
+void qo_attention_hybrid(const uint16_t *q, const uint16_t *Kc, const uint16_t *Vc, int k, const uint16_t *Ka,
+                         const uint16_t *Va, int n_app, int D, int dtype, double *out, double *w_out) {
+  if (n_app == 0) {
+    qo_attention(q, Kc, Vc, k, D, dtype, out, w_out);
+    return;
+  }
+  const size_t rows = (size_t)k + (size_t)n_app;
+  uint16_t *Kall = (uint16_t *)malloc(sizeof(uint16_t) * rows * D);
+  uint16_t *Vall = (uint16_t *)malloc(sizeof(uint16_t) * rows * D);
+  memcpy(Kall, Kc, sizeof(uint16_t) * (size_t)k * D);
+  memcpy(Vall, Vc, sizeof(uint16_t) * (size_t)k * D);
+  memcpy(Kall + (size_t)k * D, Ka, sizeof(uint16_t) * (size_t)n_app * D);
+  memcpy(Vall + (size_t)k * D, Va, sizeof(uint16_t) * (size_t)n_app * D);
+  qo_attention(q, Kall, Vall, (int)rows, D, dtype, out, w_out);
+  free(Kall);
+  free(Vall);
+}
+
+/* Sink / recent tokens and the append-only buffer of a step (all zero / NULL = plain Algorithm 1). */
+typedef struct {
+  int32_t n_sink, n_recent; /* forced members of every retrieved set: tokens [0, n_sink) and [N - n_recent, N) */
+  int32_t n_app, app_cap;   /* valid rows and row stride of the append-only buffer                             */
+  const uint16_t *K_app;    /* [P, app_cap, D]                                                                 */
+  const uint16_t *V_app;
+} qo_ext;
+
 /* ---- one QSAC step (Algorithm 1, one iteration of the loop over t) ------ */
 
 typedef struct {
@@ -252,7 +287,7 @@ typedef struct {
  * or NULL.  Outputs: out[B,Hq,D], topk_idx[P,k], hit_mask[P,k],
  * reuse_flags[P], sim[B,Hq], s_agg[P]; optional (NULL ok): kth_score[P]
  * (score of the last admitted key, NaN on reuse), scores[P,N] (NaN on reuse),
- * weights[B,Hq,k], n_filled[P].  pair_mask[P] (NULL = all) restricts the work
+ * weights[B,Hq,k+n_app], n_filled[P].  ext (NULL ok): sink / recent tokens and the append-only buffer.  pair_mask[P] (NULL = all) restricts the work
  * to the marked pairs; unmarked pairs are left untouched everywhere.
  * P = B*Hkv, pair p = b*Hkv + h; query head g of pair p is b*Hq + h*G + g.
  */
@@ -263,7 +298,9 @@ int qo_step(const qo_dims *dm, const uint16_t *q, const uint16_t *K,
             double *out, int32_t *topk_idx, uint8_t *hit_mask,
             uint8_t *reuse_flags, double *sim, double *s_agg, double *kth_score,
             double *scores, double *weights, int32_t *n_filled,
-            const uint8_t *pair_mask) {
+            const uint8_t *pair_mask, const qo_ext *ext) {
+  const int n_sink = ext ? ext->n_sink : 0, n_recent = ext ? ext->n_recent : 0;
+  const int n_app = ext ? ext->n_app : 0;
   const int G = dm->Hq / dm->Hkv, D = dm->D, k = dm->k;
   const int64_t N = dm->N;
   const int P = dm->B * dm->Hkv;
@@ -304,6 +341,8 @@ int qo_step(const qo_dims *dm, const uint16_t *q, const uint16_t *K,
       /* cache miss: retrieve, gather, replace, relabel */
       double *S = scores ? scores + (size_t)p * N : (double *)malloc(sizeof(double) * (size_t)N);
       qo_scores(qg, K + (size_t)p * N * D, G, N, D, dm->dtype, S);
+      for (int64_t n = 0; n < N; ++n)
+        if (n < n_sink || n >= N - n_recent) S[n] = INFINITY; /* sink and recent tokens always belong */
       double kth = NAN;
       int rc = qo_topk(S, N, k, tk, &kth);
       if (kth_score) kth_score[p] = kth;
@@ -329,8 +368,10 @@ int qo_step(const qo_dims *dm, const uint16_t *q, const uint16_t *K,
     /* attention over the cached rows, one query head at a time */
     for (int g = 0; g < G; ++g) {
       size_t hq = (size_t)b * dm->Hq + (size_t)h * G + g;
-      qo_attention(qg + (size_t)g * D, Ks, Vs, k, D, dm->dtype, out + hq * D,
-                   weights ? weights + hq * k : NULL);
+      qo_attention_hybrid(qg + (size_t)g * D, Ks, Vs, k,
+                          n_app ? ext->K_app + (size_t)p * ext->app_cap * D : NULL,
+                          n_app ? ext->V_app + (size_t)p * ext->app_cap * D : NULL, n_app, D, dm->dtype,
+                          out + hq * D, weights ? weights + hq * ((size_t)k + n_app) : NULL);
     }
   }
   return err;

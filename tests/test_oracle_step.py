@@ -209,3 +209,61 @@ def test_gate_reuses_on_equality(oracle):
         oracle.step(st, qa, Kb, Kb, Vb, tau, 8, code)
         r = oracle.step(st, qb, Kb, Kb, Vb, tau, 8, code)
         assert r.sim[0, 0] == 0.5 and r.reuse_flags[0] == want
+
+
+def test_hybrid_attention_is_attention_over_the_concatenation(oracle):
+    """Section 6.2: the attention reads the cached rows and the append-only buffer as one set."""
+    rng = np.random.default_rng(12)
+    bits = lambda x: W.bits(W.round_to(x, "bf16"))
+    for k, na in ((5, 1), (40, 17), (1, 64)):
+        q = bits(rng.standard_normal(128))
+        Kc, Vc = bits(rng.standard_normal((k, 128))), bits(rng.standard_normal((k, 128)))
+        Ka, Va = bits(rng.standard_normal((na, 128)) * 2), bits(rng.standard_normal((na, 128)))
+        out, w = oracle.attention_hybrid(q, Kc, Vc, Ka, Va, BF16)
+        ref = sdpa(widen_lib(q, BF16), np.concatenate([widen_lib(Kc, BF16), widen_lib(Ka, BF16)]),
+                   np.concatenate([widen_lib(Vc, BF16), widen_lib(Va, BF16)]))
+        assert np.allclose(out, ref, atol=1e-12)
+        assert w.shape == (k + na,) and w.sum() == pytest.approx(1.0, abs=1e-13)
+
+
+def test_sink_and_recent_tokens_are_always_retrieved(oracle):
+    """Section 7.1: 4 sink and 64 recent tokens stay in the cache.  The first n_sink and the last n_recent
+    tokens belong to every retrieved set; the other slots go to the best of the remaining tokens."""
+    Kb, Vb, qs, code = make_case(B=1, Hq=4, Hkv=1, N=400, steps=6)
+    Kd = widen_lib(Kb, code)
+    n_sink, n_recent, k = 4, 64, 100
+    st = oracle.State.empty(1, 4, 1, 128, k)
+    forced = list(range(n_sink)) + list(range(400 - n_recent, 400))
+    for t, q in enumerate(qs):
+        r = oracle.step(st, q, Kb, Kb, Vb, 2.0, k, code, n_sink=n_sink, n_recent=n_recent)
+        got = r.topk_idx[0].tolist()
+        assert set(forced) <= set(got)
+        qd = widen_lib(q, code)[0]
+        S = (Kd[0, 0] @ qd.T).max(axis=1)
+        middle = [n for n in range(400) if n not in forced]
+        best = sorted(middle, key=lambda n: (-S[n], n))[:k - len(forced)]
+        assert got == sorted(forced + best)
+    # with no room for anything else the set is exactly the forced tokens
+    st = oracle.State.empty(1, 4, 1, 128, 68)
+    r = oracle.step(st, qs[0], Kb, Kb, Vb, 2.0, 68, code, n_sink=4, n_recent=64)
+    assert r.topk_idx[0].tolist() == forced
+
+
+def test_step_with_append_buffer_and_k_equals_N_is_dense_over_everything(oracle):
+    Kb, Vb, qs, code = make_case(B=2, Hq=8, Hkv=2, N=80, steps=5)
+    rng = np.random.default_rng(13)
+    cap = 12
+    Ka = W.bits(W.round_to(rng.standard_normal((2, 2, cap, 128)), "bf16"))
+    Va = W.bits(W.round_to(rng.standard_normal((2, 2, cap, 128)), "bf16"))
+    st = oracle.State.empty(2, 8, 2, 128, 80)
+    for t, q in enumerate(qs):
+        n_app = t + 1                       # one generated token joins the buffer per step
+        r = oracle.step(st, q, Kb, Kb, Vb, 0.9, 80, code, K_app=Ka, V_app=Va, n_app=n_app, want_weights=True)
+        qd = widen_lib(q, code)
+        for b in range(2):
+            for hq in range(8):
+                h = hq // 4
+                Kall = np.concatenate([widen_lib(Kb, code)[b, h], widen_lib(Ka, code)[b, h, :n_app]])
+                Vall = np.concatenate([widen_lib(Vb, code)[b, h], widen_lib(Va, code)[b, h, :n_app]])
+                assert np.allclose(r.out[b, hq], sdpa(qd[b, hq], Kall, Vall), atol=1e-12)
+        assert r.weights.shape == (2, 8, 80 + n_app)
