@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--workload", default="llama3_8b_32k")
     ap.add_argument("--tau", type=float, default=None, help="override the workload's threshold")
     ap.add_argument("--flags", type=int, default=0, help="extra qsac_config.flags (e.g. 4 = ALU scoring)")
+    ap.add_argument("--decode-buffers", action="store_true",
+                    help="4 sink + 64 recent tokens kept in every set, and an append-only buffer that grows by one "
+                         "generated token per step (Sections 6.1, 6.2, 7.1)")
     ap.add_argument("--resident", type=int, default=0,
                     help="keep this many KV heads resident in HBM (Section 4.4), chosen by reuse difficulty")
     ap.add_argument("--side-stream", action="store_true",
@@ -56,6 +59,8 @@ def make_queries(w, W, n_steps):
 
 def run_steps(sess, q_dev, tau, k, lo, hi):
     for t in range(lo, hi):
+        if sess.K_app is not None:
+            sess.set_appended(t + 1)   # the token generated at step t has joined the append-only buffer
         sess.step(q_dev[t], tau, k)
 
 
@@ -127,11 +132,18 @@ def main():
     if w.host_v:
         V_dev = None  # the offload workloads keep V on the host only (and in V_res for resident heads)
     q_dev = q_all.cuda()
+    K_app = V_app = None
+    n_sink = n_recent = 0
+    if a.decode_buffers:
+        # the generated tokens' KV are synthetic too and resident beforehand; a step only raises the valid count
+        n_sink, n_recent = 4, 64
+        K_app, V_app = W.make_kv(w.B, w.Hkv, total, w.D, w.dtype, w.seed + 7, device="cuda:0")
     torch.cuda.synchronize()
 
     def session(flags):
         return Q.Session(w.B, w.Hq, w.Hkv, w.N, w.k, w.dtype, K_dev, K_src, V_src, flags=flags | a.flags,
-                         side_stream=bool(a.side_stream), V_res=V_res, res_slot=res_slot)
+                         side_stream=bool(a.side_stream), V_res=V_res, res_slot=res_slot, n_sink=n_sink,
+                         n_recent=n_recent, K_app=K_app, V_app=V_app)
 
     # ---- timed run: K steps after W warmup steps, overlapped fill, no events inside
     sess = session(0)
@@ -169,6 +181,8 @@ def main():
         "rows_filled_from_host_per_step": ((d["slot_misses"] - d["resident_rows"]) / K_steps
                                            if (w.host_k or w.host_v) else 0.0),
     }
+    if a.decode_buffers:
+        result["config"].update({"n_sink": n_sink, "n_recent": n_recent, "append_rows_at_end": total})
     if a.resident:
         result["config"]["resident_kv_heads"] = sorted(hard)
         result["config"]["reuse_difficulty"] = [round(x, 4) for x in D]

@@ -86,6 +86,12 @@ typedef struct {
   void *workspace;              /* DEVICE, 256-byte aligned, >= qsac_workspace_bytes(); caller-owned       */
   size_t workspace_bytes;
   int32_t flags;
+  /* Sink and recent tokens (Section 7.1: kept in the cache persistently): the first n_sink and the last
+     n_recent of the N context tokens rank above every score, so every retrieved set contains them
+     (k >= n_sink + n_recent).  0 = none. */
+  int32_t n_sink, n_recent;
+  /* Rows per KV head of the append-only buffer (Sections 6.1, 6.2), 0 = none; see qsac_step_args.K_app. */
+  int32_t append_capacity;
 } qsac_config;
 
 /* Byte offsets of the library's arrays inside the workspace (for tests and tools that inspect them). */
@@ -140,6 +146,12 @@ typedef struct {
   const void *V_res;         /* DEVICE e [B,n_res,N,D] or NULL  full V of the resident KV heads          */
   const int8_t *res_slot;    /* HOST [n_kv_heads] or NULL       index in V_res, -1 = not resident         */
   int32_t n_res;             /* resident KV heads, 1 <= n_res <= n_kv_heads when res_slot is given       */
+  /* Append-only buffer (Sections 6.1, 6.2): KV of the tokens generated during decoding, appended by the
+     caller before the step.  The hybrid attention reads its n_app valid rows in place next to the k cached
+     rows; they are not scored, selected or cached.  n_app = 0 = none. */
+  const void *K_app;         /* DEVICE e [B,Hkv,append_capacity,D]                                        */
+  const void *V_app;         /* DEVICE e [B,Hkv,append_capacity,D]                                        */
+  int32_t n_app;             /* valid rows, 0 <= n_app <= append_capacity                                 */
 } qsac_step_args;
 
 /* Cumulative since init / reset, summed over pairs. */

@@ -31,7 +31,7 @@ class qsac_config(C.Structure):
                 ("n_ctx", C.c_int64), ("k_max", C.c_int32), ("dtype", C.c_int32),
                 ("q_head_importance", C.POINTER(C.c_float)), ("stream_main", C.c_void_p),
                 ("stream_side", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
-                ("flags", C.c_int32)]
+                ("flags", C.c_int32), ("n_sink", C.c_int32), ("n_recent", C.c_int32), ("append_capacity", C.c_int32)]
 
 
 class qsac_ws_layout(C.Structure):
@@ -46,7 +46,8 @@ class qsac_step_args(C.Structure):
                 ("K_slots", C.c_void_p), ("V_slots", C.c_void_p), ("slot_idx", C.c_void_p), ("prev_q", C.c_void_p),
                 ("tau", C.POINTER(C.c_float)), ("n_tau", C.c_int32), ("k", C.c_int32), ("out", C.c_void_p),
                 ("topk_idx", C.c_void_p), ("hit_mask", C.c_void_p), ("reuse_flags", C.c_void_p), ("sim", C.c_void_p),
-                ("V_res", C.c_void_p), ("res_slot", C.POINTER(C.c_int8)), ("n_res", C.c_int32)]
+                ("V_res", C.c_void_p), ("res_slot", C.POINTER(C.c_int8)), ("n_res", C.c_int32),
+                ("K_app", C.c_void_p), ("V_app", C.c_void_p), ("n_app", C.c_int32)]
 
 
 class qsac_stats(C.Structure):
@@ -187,8 +188,10 @@ def qsac_free(ctx) -> None:
         raise QsacError(rc, "qsac_free")
 
 
-def make_config(B, Hq, Hkv, N, k_max, dtype, flags=0, importance=None) -> qsac_config:
+def make_config(B, Hq, Hkv, N, k_max, dtype, flags=0, importance=None, n_sink=0, n_recent=0,
+                append_capacity=0) -> qsac_config:
     cfg = qsac_config()
+    cfg.n_sink, cfg.n_recent, cfg.append_capacity = n_sink, n_recent, append_capacity
     cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = B, Hq, Hkv, QSAC_HEAD_DIM
     cfg.n_ctx, cfg.k_max, cfg.dtype, cfg.flags = N, k_max, dtype, flags
     if importance is not None:
@@ -206,7 +209,7 @@ class Session:
     """
 
     def __init__(self, B, Hq, Hkv, N, k_max, dtype: str, K_dev, K_src, V_src, flags=0, importance=None,
-                 side_stream=False, V_res=None, res_slot=None):
+                 side_stream=False, V_res=None, res_slot=None, n_sink=0, n_recent=0, K_app=None, V_app=None):
         """V_res [B,n_res,N,128] (device) and res_slot [Hkv] make the KV heads with res_slot >= 0 resident."""
         import torch
         from .workload import DTYPE_CODES, TORCH_DTYPES
@@ -226,7 +229,13 @@ class Session:
         assert K_dev.is_cuda
         self.main = torch.cuda.Stream(device=dev)
         self.side = torch.cuda.Stream(device=dev) if side_stream else None
-        cfg = make_config(B, Hq, Hkv, N, k_max, DTYPE_CODES[dtype], flags, importance)
+        self.K_app, self.V_app, self.n_app = K_app, V_app, 0
+        cap = 0
+        if K_app is not None:
+            cap = K_app.shape[2]
+            for t in (K_app, V_app):
+                assert t.is_cuda and t.is_contiguous() and t.dtype == tdt and t.shape == (B, Hkv, cap, 128)
+        cfg = make_config(B, Hq, Hkv, N, k_max, DTYPE_CODES[dtype], flags, importance, n_sink, n_recent, cap)
         nbytes = qsac_workspace_bytes(cfg)
         if nbytes == 0:
             raise QsacError(QSAC_EINVAL, "qsac_workspace_bytes")
@@ -267,12 +276,19 @@ class Session:
         a.prev_q, a.tau, a.n_tau, a.k = self.prev_q.data_ptr(), C.cast(tau_arr, C.POINTER(C.c_float)), len(taus), k
         a.out, a.topk_idx, a.hit_mask = self.out.data_ptr(), self.topk_idx.data_ptr(), self.hit_mask.data_ptr()
         a.reuse_flags, a.sim = self.reuse_flags.data_ptr(), self.sim.data_ptr()
+        if self.n_app:
+            a.K_app, a.V_app, a.n_app = self.K_app.data_ptr(), self.V_app.data_ptr(), self.n_app
         if self.V_res is not None:
             rs = (C.c_int8 * self.Hkv)(*self.res_slot)
             a._keep_rs = rs
             a.V_res, a.res_slot, a.n_res = self.V_res.data_ptr(), C.cast(rs, C.POINTER(C.c_int8)), self.V_res.shape[1]
         self._last_q = q  # keep the tensor alive until the stream has consumed it
         qsac_step(self.ctx, a)
+
+    def set_appended(self, n_app: int):
+        """Number of valid rows of the append-only buffer from the next step on (the caller has written them)."""
+        assert self.K_app is not None and 0 <= n_app <= self.K_app.shape[2]
+        self.n_app = n_app
 
     def sync(self):
         self.main.synchronize()

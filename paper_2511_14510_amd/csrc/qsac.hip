@@ -35,6 +35,8 @@ int check_config(const qsac_config* c) {
   if (c->n_ctx < 1 || c->n_ctx > (int64_t(1) << 20)) return QSAC_ERANGE;
   if (c->k_max < 1 || c->k_max > c->n_ctx) return QSAC_ERANGE;
   if ((int64_t)c->batch * c->n_kv_heads > 65535) return QSAC_ERANGE;  // grid.y
+  if (c->append_capacity < 0 || c->append_capacity > (1 << 20)) return QSAC_ERANGE;
+  if (c->n_sink < 0 || c->n_recent < 0 || (int64_t)c->n_sink + c->n_recent > c->k_max) return QSAC_ERANGE;
   if (c->flags & ~(QSAC_FLAG_DRY_RUN | QSAC_FLAG_SERIAL | QSAC_FLAG_SCORE_VALU | QSAC_FLAG_PROFILE | QSAC_FLAG_FILL_KERNEL)) return QSAC_EINVAL;
   if (c->q_head_importance)
     for (int i = 0; i < c->n_q_heads; ++i)
@@ -59,7 +61,7 @@ void make_layout(const qsac_config* c, qsac_ws_layout* L) {
   const size_t G = (size_t)(c->n_q_heads / c->n_kv_heads);
   const size_t n_pad = align_up((size_t)c->n_ctx, kSelChunk);
   const size_t words = n_pad / 32;
-  const size_t splits = ((size_t)c->k_max + 63) / 64;  // rows per split is never below 64
+  const size_t splits = ((size_t)c->k_max + (size_t)c->append_capacity + 63) / 64;  // rows per split >= 64
   size_t off = 0;
   auto take = [&](size_t bytes) {
     size_t o = off;
@@ -157,15 +159,15 @@ void launch_score(const qsac_ctx* c, const qsac_step_args* a, u32* keys, u32* hi
   if (c->small) {
     dim3 grid((unsigned)((N + kScoreRowsSmall - 1) / kScoreRowsSmall), (unsigned)c->P);
     if (valu)
-      qsac_score_valu_kernel<DT, G, kScoreRowsSmall, false><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad);
+      qsac_score_valu_kernel<DT, G, kScoreRowsSmall, false><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
     else
-      qsac_score_mfma_kernel<DT, G, kScoreRowsSmall, false><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad);
+      qsac_score_mfma_kernel<DT, G, kScoreRowsSmall, false><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
   } else {
     dim3 grid((unsigned)((N + kScoreRowsLarge - 1) / kScoreRowsLarge), (unsigned)c->P);
     if (valu)
-      qsac_score_valu_kernel<DT, G, kScoreRowsLarge, true><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad);
+      qsac_score_valu_kernel<DT, G, kScoreRowsLarge, true><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
     else
-      qsac_score_mfma_kernel<DT, G, kScoreRowsLarge, true><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad);
+      qsac_score_mfma_kernel<DT, G, kScoreRowsLarge, true><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
   }
 }
 
@@ -178,12 +180,16 @@ void launch_attn(const qsac_ctx* c, const qsac_step_args* a, hipStream_t stream,
   auto Vs = static_cast<v4u*>(a->V_slots);
   if (c->fill_kernel)
     qsac_attn_kernel<DT, G, false><<<grid, 256, 0, stream>>>(
-        q, Ks, Vs, src, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads,
-        c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits, which);
+        q, Ks, Vs, src, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out,
+        static_cast<const v4u*>(a->K_app), static_cast<const v4u*>(a->V_app), a->n_app, c->cfg.append_capacity,
+        c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits,
+        which);
   else
     qsac_attn_kernel<DT, G, true><<<grid, 256, 0, stream>>>(
-        q, Ks, Vs, src, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out, c->cfg.n_q_heads,
-        c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits, which);
+        q, Ks, Vs, src, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out,
+        static_cast<const v4u*>(a->K_app), static_cast<const v4u*>(a->V_app), a->n_app, c->cfg.append_capacity,
+        c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits,
+        which);
 }
 
 // Dispatch on (dtype, G) to the instantiated kernels.
@@ -319,6 +325,12 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   const void* al[] = {a->q, a->K_dev, a->K_src, a->V_src, a->K_slots, a->V_slots, a->slot_idx, a->prev_q, a->out, a->topk_idx};
   for (const void* ptr : al)
     if (!aligned16(ptr)) return QSAC_EALIGN;
+  if (a->n_app < 0 || a->n_app > c->cfg.append_capacity) return QSAC_ERANGE;
+  if (a->n_app > 0) {
+    if (!a->K_app || !a->V_app) return QSAC_ENULL;
+    if (!aligned16(a->K_app) || !aligned16(a->V_app)) return QSAC_EALIGN;
+  }
+  if (a->k < c->cfg.n_sink + c->cfg.n_recent) return QSAC_ERANGE;
   if (a->res_slot) {
     if (!a->V_res) return QSAC_ENULL;
     if (a->n_res < 1 || a->n_res > c->cfg.n_kv_heads) return QSAC_ERANGE;
@@ -382,8 +394,8 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     qsac_gate_kernel<1><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
                                            a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max);
-  const int rows = attn_rows(P, k);
-  const int n_splits = (k + rows - 1) / rows;
+  const int rows = attn_rows(P, k + a->n_app);
+  const int n_splits = (k + a->n_app + rows - 1) / rows;
   dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
   dim3 attn_grid((unsigned)n_splits, (unsigned)P);
   auto fill_on = [&](hipStream_t s) {

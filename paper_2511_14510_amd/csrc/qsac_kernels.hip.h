@@ -82,6 +82,16 @@ __device__ __forceinline__ void fill_rows_of(const FillSrc& f, int p, int Hkv, i
 __device__ __forceinline__ u32 fbits(float f) { return __builtin_bit_cast(u32, f); }
 __device__ __forceinline__ float bitsf(u32 u) { return __builtin_bit_cast(float, u); }
 
+// Key of a token at position n of N: sink tokens (the first n_sink) and recent tokens (the last
+// n_recent) are kept in the cache persistently (Section 7.1 of the paper), i.e. they rank above
+// every score; positions at and past N get key 0, below every score.
+__device__ __forceinline__ u32 ordered_key(float f);
+__device__ __forceinline__ u32 token_key(float score, int64_t n, int64_t N, int n_sink, int n_recent) {
+  if (n >= N) return 0u;
+  if (n < n_sink || n >= N - n_recent) return 0xffffffffu;
+  return ordered_key(score);
+}
+
 // Order-preserving image of a finite fp32: a > b  <=>  key(a) > key(b); -0 ranks as +0.
 __device__ __forceinline__ u32 ordered_key(float f) {
   u32 u = fbits(f);
@@ -367,7 +377,8 @@ __device__ __forceinline__ void score_hist_epilogue(const u32* s_keys, u32* s_hi
 template <int DT, int G, int ROWS, bool HIST>
 __global__ __launch_bounds__(256) void qsac_score_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint8_t* __restrict__ reuse_flags,
-    u32* __restrict__ keys, u32* __restrict__ hist, int Hq, int Hkv, int64_t N, int64_t n_pad) {
+    u32* __restrict__ keys, u32* __restrict__ hist, int Hq, int Hkv, int64_t N, int64_t n_pad, int n_sink,
+    int n_recent) {
   const int p = blockIdx.y;
   if (reuse_flags[p]) return;
   __shared__ __attribute__((aligned(16))) unsigned char s_tile[4][2][16 * kTilePitch];
@@ -425,7 +436,7 @@ __global__ __launch_bounds__(256) void qsac_score_mfma_kernel(
         s = fmaxf(s, t);
       }
       const int r = wrow + (t0 + u) * 16 + m;
-      const u32 key = (row0 + r < N) ? ordered_key(s) : 0u;
+      const u32 key = token_key(s, row0 + r, N, n_sink, n_recent);
       if (quarter == 0) {
         if (HIST)
           s_keys[r] = key;
@@ -443,7 +454,8 @@ __global__ __launch_bounds__(256) void qsac_score_mfma_kernel(
 template <int DT, int G, int ROWS, bool HIST>
 __global__ __launch_bounds__(256) void qsac_score_valu_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint8_t* __restrict__ reuse_flags,
-    u32* __restrict__ keys, u32* __restrict__ hist, int Hq, int Hkv, int64_t N, int64_t n_pad) {
+    u32* __restrict__ keys, u32* __restrict__ hist, int Hq, int Hkv, int64_t N, int64_t n_pad, int n_sink,
+    int n_recent) {
   const int p = blockIdx.y;
   if (reuse_flags[p]) return;
   __shared__ u32 s_hist[HIST ? kBins : 1];
@@ -485,7 +497,7 @@ __global__ __launch_bounds__(256) void qsac_score_valu_kernel(
 #pragma unroll
         for (int g = 1; g < G; ++g) best = fmaxf(best, row16_sum(dot8<DT>(qf[g], kv[t][u])));
         const int rr = wrow + (t0 + t) * 16 + r * 4 + u;
-        out[u] = (row0 + rr < N) ? ordered_key(best) : 0u;
+        out[u] = token_key(best, row0 + rr, N, n_sink, n_recent);
       }
       if (c == 0) {
         u32* dst = (HIST ? s_keys : kout) + wrow + (t0 + t) * 16 + r * 4;
@@ -993,7 +1005,8 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
     const uint16_t* __restrict__ q, v4u* __restrict__ K_slots, v4u* __restrict__ V_slots, FillSrc src,
     const int* __restrict__ fetch_tok,
     const int* __restrict__ miss_count, const uint8_t* __restrict__ reuse_flags, float* __restrict__ part_ml,
-    float* __restrict__ part_acc, float* __restrict__ out, int Hq, int Hkv, int64_t N, int k, int k_max, int rows,
+    float* __restrict__ part_acc, float* __restrict__ out, const v4u* __restrict__ K_app,
+    const v4u* __restrict__ V_app, int n_app, int app_cap, int Hq, int Hkv, int64_t N, int k, int k_max, int rows,
     int n_splits, int max_splits, int which) {
   const int p = blockIdx.y, split = blockIdx.x;
   if (!pair_selected(which, reuse_flags, p)) return;
@@ -1016,6 +1029,10 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
   fill_rows_of(src, p, Hkv, N, Ks, Vs);
   const int* ft = fetch_tok + (size_t)p * k_max;
   const bool fetch = FETCH && miss_count[p] > 0;  // uniform over the workgroup
+  // Rows k .. k + n_app - 1 of the attended set are the valid rows of the append-only buffer (KV of
+  // the tokens generated during decoding, Sections 6.1 and 6.2 of the paper), read in place.
+  const v4u* Ka = K_app + (size_t)p * app_cap * kRowU4;
+  const v4u* Va = V_app + (size_t)p * app_cap * kRowU4;
 
   const float kScale = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
   const float kNegInf = -__builtin_inff();
@@ -1032,7 +1049,7 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
     for (int d = 0; d < 8; ++d) acc[g][d] = 0.f;
 
   const int s_begin = split * rows;
-  const int s_end = min(s_begin + rows, k);
+  const int s_end = min(s_begin + rows, k + n_app);
 
   // tokens to fetch for this lane's four rows of the tile at t0 (-1: the row is in its slot).
   // Rows past the end of the range repeat the last row, so that what is loaded is always real data.
@@ -1041,16 +1058,17 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
     for (int j = 0; j < 4; ++j) {
       int row = t0 + 4 * j + quarter;
       row = row < s_end ? row : s_end - 1;
-      tok[j] = fetch ? ft[row] : -1;
+      tok[j] = (fetch && row < k) ? ft[row] : -1;
     }
   };
   // issue the loads of this lane's four K (or V) rows of the tile at t0
-  auto load_tile = [&](int t0, const int (&tok)[4], v4u (&dst)[4], const v4u* slots, const v4u* src) {
+  auto load_tile = [&](int t0, const int (&tok)[4], v4u (&dst)[4], const v4u* slots, const v4u* src,
+                       const v4u* app) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int row = t0 + 4 * j + quarter;
       row = row < s_end ? row : s_end - 1;
-      const v4u* from = slots + (size_t)row * kRowU4;
+      const v4u* from = row < k ? slots + (size_t)row * kRowU4 : app + (size_t)(row - k) * kRowU4;
       if (FETCH && tok[j] >= 0) from = src + (size_t)tok[j] * kRowU4;
       dst[j] = from[m];
     }
@@ -1136,20 +1154,20 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
     int t0 = s_begin + wave * 16;  // uniform over the wave: every lane takes part in the MFMAs and DPP
     if (t0 < s_end) {
       load_tok(t0, tokC);
-      load_tile(t0, tokC, kk, Kp, Ks);
-      load_tile(t0, tokC, vv, Vp, Vs);
+      load_tile(t0, tokC, kk, Kp, Ks, Ka);
+      load_tile(t0, tokC, vv, Vp, Vs, Va);
       if (t0 + 64 < s_end) load_tok(t0 + 64, tokN);
     }
     for (; t0 < s_end; t0 += 64) {
       const bool more = t0 + 64 < s_end;
       store_fetched(t0, tokC, kk, Kp);
       stage_k(kk);
-      if (more) load_tile(t0 + 64, tokN, kk, Kp, Ks);
+      if (more) load_tile(t0 + 64, tokN, kk, Kp, Ks, Ka);
       softmax_tile(t0);
       store_fetched(t0, tokC, vv, Vp);
       fold_v(vv);
       if (more) {
-        load_tile(t0 + 64, tokN, vv, Vp, Vs);
+        load_tile(t0 + 64, tokN, vv, Vp, Vs, Va);
 #pragma unroll
         for (int j = 0; j < 4; ++j) tokC[j] = tokN[j];
         if (t0 + 128 < s_end) load_tok(t0 + 128, tokN);

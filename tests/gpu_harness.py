@@ -34,10 +34,12 @@ def host_state(sess: Q.Session) -> oracle.State:
 class Parity:
     """Runs steps on a Session and checks each against the oracle."""
 
-    def __init__(self, sess: Q.Session, dtype: str, Kb, Ksrc_b, Vsrc_b, importance=None, pair_mask=None):
+    def __init__(self, sess: Q.Session, dtype: str, Kb, Ksrc_b, Vsrc_b, importance=None, pair_mask=None,
+                 n_sink=0, n_recent=0, Kapp_b=None, Vapp_b=None):
         self.s, self.dtype, self.code = sess, dtype, W.DTYPE_CODES[dtype]
         self.Kb, self.Ksb, self.Vsb = Kb, Ksrc_b, Vsrc_b
         self.importance = importance
+        self.n_sink, self.n_recent, self.Kapp_b, self.Vapp_b = n_sink, n_recent, Kapp_b, Vapp_b
         self.pair_mask = None if pair_mask is None else np.asarray(pair_mask, np.uint8)
         self.pairs = list(range(sess.P)) if pair_mask is None else [p for p in range(sess.P) if pair_mask[p]]
         self.n_reuse = self.n_miss = self.n_band = 0
@@ -61,7 +63,8 @@ class Parity:
         s.step(qt.cuda(), tau, k)
         s.sync()
         r = oracle.step(st, qb, self.Kb, self.Ksb, self.Vsb, tau, k, self.code, importance=self.importance,
-                        want_scores=True, pair_mask=self.pair_mask)
+                        want_scores=True, pair_mask=self.pair_mask, n_sink=self.n_sink, n_recent=self.n_recent,
+                        K_app=self.Kapp_b, V_app=self.Vapp_b, n_app=s.n_app)
         after = host_state(s)
         g_reuse = s.reuse_flags.cpu().numpy().reshape(-1)
         g_topk = s.topk_idx.cpu().numpy().reshape(s.P, k)
@@ -88,7 +91,8 @@ class Parity:
                 kth = r.kth_score[p]
                 diff = np.setxor1d(g_topk[p], r.topk_idx[p])
                 sc = r.scores[p][diff]
-                assert np.all(np.abs(sc - kth) <= BAND * abs(kth)), f"{where}: index sets differ outside the band"
+                assert np.isfinite(kth) and np.all(np.abs(sc - kth) <= BAND * abs(kth)), \
+                    f"{where}: index sets differ outside the band"
                 assert np.all(np.diff(g_topk[p]) > 0), where
                 self.n_band += 1
             old = set(before.slot_idx[p, :k].tolist()) if before.valid[p] else set()
@@ -124,7 +128,11 @@ class Parity:
                 if same_set:
                     ref = r.out[b, hq]
                 else:
-                    ref, _ = oracle.attention(qb[b, hq], after.K_slots[p, :k], after.V_slots[p, :k], self.code)
+                    if s.n_app:
+                        ref, _ = oracle.attention_hybrid(qb[b, hq], after.K_slots[p, :k], after.V_slots[p, :k],
+                                                         self.Kapp_b[b, h, :s.n_app], self.Vapp_b[b, h, :s.n_app], self.code)
+                    else:
+                        ref, _ = oracle.attention(qb[b, hq], after.K_slots[p, :k], after.V_slots[p, :k], self.code)
                 err = float(np.abs(g_out[b, hq] - ref).max())
                 self.max_err = max(self.max_err, err)
                 assert err <= OUT_TOL, f"{where} head {hq}: attention max-abs error {err:.3e}"

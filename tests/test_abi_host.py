@@ -96,7 +96,7 @@ def test_workspace_checks_without_dry_run(lib):
 def _args(**over):
     a = Q.qsac_step_args()
     for f, _ in Q.qsac_step_args._fields_:
-        if f not in ("tau", "n_tau", "k", "V_res", "res_slot", "n_res"):
+        if f not in ("tau", "n_tau", "k", "V_res", "res_slot", "n_res", "K_app", "V_app", "n_app"):
             setattr(a, f, 0x10000)
     tau = (C.c_float * 2)(0.9, 0.8)
     a._keep = tau
@@ -133,6 +133,7 @@ def test_step_validation_on_a_dry_run_context(lib):
     assert step(_args(res_slot=rsp, n_res=3, V_res=0x20000)) == Q.QSAC_ERANGE
     bad = (C.c_int8 * 2)(1, -1)
     assert step(_args(res_slot=C.cast(bad, C.POINTER(C.c_int8)), n_res=1, V_res=0x20000)) == Q.QSAC_ERANGE
+    assert step(_args(n_app=1, K_app=0x30000, V_app=0x40000)) == Q.QSAC_ERANGE   # no append capacity configured
     assert step(_args(k=128)) == Q.QSAC_ESTATE                     # k changed without a reset
     Q.qsac_reset(ctx)
     assert step(_args(k=128)) == Q.QSAC_OK
@@ -188,3 +189,21 @@ def test_reuse_difficulty_matches_the_oracle(lib, oracle):
     assert np.allclose(got, want, atol=6e-8)
     with pytest.raises(Q.QsacError):
         Q.qsac_reuse_difficulty(tau, sim, 0.0)
+
+
+def test_sink_recent_and_append_validation(lib):
+    cfg = Q.make_config(1, 8, 2, 4096, 256, Q.QSAC_F16, Q.QSAC_FLAG_DRY_RUN, n_sink=4, n_recent=64, append_capacity=32)
+    assert Q.qsac_workspace_layout(cfg).max_splits == (256 + 32 + 63) // 64
+    ctx = Q.qsac_init(cfg)
+    step = lambda a: lib.qsac_step(ctx, C.byref(a))
+    assert step(_args(k=67)) == Q.QSAC_ERANGE                      # no room for the 68 persistent tokens
+    assert step(_args(k=68)) == Q.QSAC_OK
+    Q.qsac_reset(ctx)
+    assert step(_args(n_app=33, K_app=0x30000, V_app=0x40000)) == Q.QSAC_ERANGE
+    assert step(_args(n_app=5, K_app=None, V_app=0x40000)) == Q.QSAC_ENULL
+    assert step(_args(n_app=5, K_app=0x30008, V_app=0x40000)) == Q.QSAC_EALIGN
+    assert step(_args(n_app=32, K_app=0x30000, V_app=0x40000)) == Q.QSAC_OK
+    Q.qsac_free(ctx)
+    for kw in (dict(n_sink=-1), dict(n_sink=200, n_recent=100), dict(append_capacity=-5)):
+        bad = Q.make_config(1, 8, 2, 4096, 256, Q.QSAC_F16, Q.QSAC_FLAG_DRY_RUN, **kw)
+        assert Q.qsac_workspace_bytes(bad) == 0

@@ -116,6 +116,44 @@ def test_resident_heads_never_touch_their_host_rows(H, flags):
     sess.close()
 
 
+@pytest.mark.parametrize("flags,N", [(0, 6000), (Q.QSAC_FLAG_SCORE_VALU, 6000), (0, 70001)])
+def test_sink_recent_tokens_and_append_buffer(H, flags, N):
+    """Section 7.1 / 6.2: 4 sink and 64 recent tokens are members of every retrieved set, and the attention
+    runs over the k cached rows plus the append-only buffer, which grows by one generated token per step."""
+    B, Hq, Hkv, k, cap = 2, 8, 2, 200, 40
+    n_sink, n_recent = 4, 64
+    K, V = W.make_kv(B, Hkv, N, 128, "bf16", 41)
+    Ka, Va = W.make_kv(B, Hkv, cap, 128, "bf16", 42)
+    sess = Q.Session(B, Hq, Hkv, N, k, "bf16", K.cuda(), K.cuda(), V.cuda(), flags=flags, n_sink=n_sink,
+                     n_recent=n_recent, K_app=Ka.cuda(), V_app=Va.cuda())
+    par = H.Parity(sess, "bf16", W.bits(K), W.bits(K), W.bits(V), n_sink=n_sink, n_recent=n_recent,
+                   Kapp_b=W.bits(Ka), Vapp_b=W.bits(Va))
+    chain = W.QueryChain(B, Hq, 128, 0.95, 41)
+    forced = set(range(n_sink)) | set(range(N - n_recent, N))
+    for t in range(cap):
+        sess.set_appended(t + 1)
+        par.step(chain.next(), 0.9, k, label=f"append step {t}")
+        for p in range(B * Hkv):
+            assert forced <= set(sess.topk_idx.view(B * Hkv, k)[p].tolist())
+    assert par.n_reuse > 0 and par.n_miss > B * Hkv
+    sess.close()
+
+
+def test_only_persistent_tokens_fit(H):
+    """k = n_sink + n_recent: the retrieved set is exactly the persistent tokens, whatever the scores."""
+    N, k = 3000, 68
+    sess, Kb, Ksb, Vsb = H.make_session(1, 4, 1, N, k, "bf16", seed=43)
+    sess.close()
+    K, V = W.make_kv(1, 1, N, 128, "bf16", 43)
+    sess = Q.Session(1, 4, 1, N, k, "bf16", K.cuda(), K.cuda(), V.cuda(), n_sink=4, n_recent=64)
+    par = H.Parity(sess, "bf16", W.bits(K), W.bits(K), W.bits(V), n_sink=4, n_recent=64)
+    chain = W.QueryChain(1, 4, 128, 0.5, 43)
+    for t in range(3):
+        par.step(chain.next(), 2.0, k, label=f"persistent only step {t}")
+        assert sess.topk_idx.view(-1).tolist() == list(range(4)) + list(range(N - 64, N))
+    sess.close()
+
+
 def test_per_head_tau_and_importance(H):
     imp = [0.2, 1.0, 3.0, 0.7, 1.0, 1.0, 0.1, 2.5]
     par = run_chain(H, B=2, Hq=8, Hkv=2, N=2000, k=100, k_max=100, dtype="bf16", steps=16, tau=[0.95, 0.8],
