@@ -156,6 +156,25 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
   return v;
 }
 
+// Sum of a double over the 64 lanes of a wave, delivered in lane 63 (other lanes hold partial
+// prefixes).  Same DPP ladder as wave_inclusive_scan, applied to both halves of the value.
+template <int CTRL, int ROW_MASK, bool BOUND>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const unsigned long long u = __builtin_bit_cast(unsigned long long, v);
+  const u32 lo = (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)u, CTRL, ROW_MASK, 0xf, BOUND);
+  const u32 hi = (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)(u >> 32), CTRL, ROW_MASK, 0xf, BOUND);
+  return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);  // masked-off rows read +0.0
+}
+__device__ __forceinline__ double wave_sum_f64_lane63(double v) {
+  v += dpp_f64<0x111, 0xf, true>(v);
+  v += dpp_f64<0x112, 0xf, true>(v);
+  v += dpp_f64<0x114, 0xf, true>(v);
+  v += dpp_f64<0x118, 0xf, true>(v);
+  v += dpp_f64<0x142, 0xa, false>(v);
+  v += dpp_f64<0x143, 0xc, false>(v);
+  return v;
+}
+
 // Exclusive prefix sum of one int per thread over a workgroup of NW wavefronts; *total gets the sum.
 // Contains barriers: every thread of the workgroup must call it.
 template <int NW>
@@ -295,13 +314,10 @@ __global__ __launch_bounds__(256) void qsac_gate_kernel(
     double a0 = (double)lo16<DT>(a), a1 = (double)hi16<DT>(a);
     double c0 = (double)lo16<DT>(c), c1 = (double)hi16<DT>(c);
     double ab = a0 * c0 + a1 * c1, aa = a0 * a0 + a1 * a1, cc = c0 * c0 + c1 * c1;
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-      ab += __shfl_xor(ab, d);
-      aa += __shfl_xor(aa, d);
-      cc += __shfl_xor(cc, d);
-    }
-    if (lane == 0) {
+    ab = wave_sum_f64_lane63(ab);
+    aa = wave_sum_f64_lane63(aa);
+    cc = wave_sum_f64_lane63(cc);
+    if (lane == 63) {
       double s = (aa == 0.0 || cc == 0.0) ? -1.0 : ab / (sqrt(aa) * sqrt(cc));
       s_sim[g] = s;
       if (sim_out) sim_out[head0 + g] = (float)s;
@@ -1248,15 +1264,32 @@ __global__ __launch_bounds__(128) void qsac_combine_kernel(const float* __restri
   const float kNegInf = -__builtin_inff();
   const float* ml = part_ml + (size_t)pg * max_splits * 2;
   const float* pa = part_acc + (size_t)pg * max_splits * kD;
-  float M = kNegInf;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml[s * 2]);
-  float L = 0.f, A = 0.f;
-#pragma unroll 8
-  for (int s = 0; s < n_splits; ++s) {
-    const float ms = ml[s * 2];
-    const float wt = (ms == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
-    L += ml[s * 2 + 1] * wt;
-    A += pa[(size_t)s * kD + d] * wt;
+  // eight splits at a time: their loads are all issued before the first is used, and the chunks
+  // are merged online in split order
+  float M = kNegInf, L = 0.f, A = 0.f;
+  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+    float mv[8], lv[8], av[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int sp = s0 + i;
+      const bool in = sp < n_splits;
+      mv[i] = in ? ml[sp * 2] : kNegInf;
+      lv[i] = in ? ml[sp * 2 + 1] : 0.f;
+      av[i] = in ? pa[(size_t)sp * kD + d] : 0.f;
+    }
+    float Mc = M;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) Mc = fmaxf(Mc, mv[i]);
+    const float w0 = (M == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(M - Mc);
+    L *= w0;
+    A *= w0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float wt = (mv[i] == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mv[i] - Mc);
+      L += lv[i] * wt;
+      A += av[i] * wt;
+    }
+    M = Mc;
   }
   const int b = p / Hkv, h = p % Hkv;
   out[((size_t)b * Hq + (size_t)h * G + g) * kD + d] = A / L;

@@ -140,7 +140,7 @@ class Parity:
 
 
 def make_session_on_gpu(w, flags=0, side_stream=False):
-    """A BASELINE-sized workload: K, V drawn on the GPU, copied once to pinned host memory (which
+    """A full-size benchmark workload: K, V drawn on the GPU, copied once to pinned host memory (which
     is both the fill source of the offload workloads and what the oracle reads)."""
     K_dev, V_dev = W.make_kv(w.B, w.Hkv, w.N, w.D, w.dtype, w.seed, device="cuda:0")
     K_host = torch.empty(K_dev.shape, dtype=K_dev.dtype, pin_memory=True).copy_(K_dev)

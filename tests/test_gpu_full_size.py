@@ -1,4 +1,4 @@
-"""Parity at the BASELINE workloads' full sizes, through the same Session / launch configuration
+"""Parity at the full sizes of the five benchmark workloads, through the same Session / launch configuration
 bench.py times.  The oracle follows a seeded sample of (batch, KV head) pairs every step (all pairs on
 the first step, where every head misses), starting each step from the GPU's own cache state."""
 import numpy as np

@@ -38,7 +38,7 @@ def run_chain(H, B, Hq, Hkv, N, k, k_max, dtype, steps, tau=0.9, rho=0.95, seed=
 
 
 def test_tiny_config_full_run(H):
-    """BASELINE config 1 in full: 1 x 8q/2kv, N=4096, k=256, fp16, tau=0.9, 64 steps."""
+    """The tiny workload in full: 1 x 8q/2kv, N=4096, k=256, fp16, tau=0.9, 64 steps."""
     w = W.CONFIGS["tiny"]
     par = run_chain(H, w.B, w.Hq, w.Hkv, w.N, w.k, w.k, w.dtype, w.steps, w.tau, w.rho, w.seed)
     assert 0.3 < par.n_reuse / (par.n_reuse + par.n_miss) < 0.95
