@@ -177,6 +177,7 @@ def main():
                    "side_stream": (("fill kernel" if (a.flags & Q.QSAC_FLAG_FILL_KERNEL) else "attention of reused heads")
                                    if a.side_stream else None)},
         "reuse_rate": reuse_rate, "slot_hit_rate": slot_hit_rate,
+        "guided_select_rate": d["guided_selects"] / d["miss_heads"] if d["miss_heads"] else None,
         "rows_filled_per_step": d["slot_misses"] / K_steps,
         "rows_filled_from_host_per_step": ((d["slot_misses"] - d["resident_rows"]) / K_steps
                                            if (w.host_k or w.host_v) else 0.0),

@@ -162,7 +162,8 @@ typedef struct {
   uint64_t slot_hits;    /* rows of a fresh top-k that were cached      */
   uint64_t slot_misses;  /* rows filled from the fill sources           */
   uint64_t resident_rows;/* of those, rows of resident heads (from HBM) */
-  uint64_t reserved[2];
+  uint64_t guided_selects;/* misses whose top-k was taken from the candidates above a sampled bound */
+  uint64_t reserved[1];
 } qsac_stats;
 
 /* Workspace size for a configuration (pure host function; 0 if the configuration is invalid). */

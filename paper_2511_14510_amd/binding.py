@@ -53,7 +53,7 @@ class qsac_step_args(C.Structure):
 class qsac_stats(C.Structure):
     _fields_ = [("steps", C.c_uint64), ("reuse_heads", C.c_uint64), ("miss_heads", C.c_uint64),
                 ("slot_hits", C.c_uint64), ("slot_misses", C.c_uint64), ("resident_rows", C.c_uint64),
-                ("reserved", C.c_uint64 * 2)]
+                ("guided_selects", C.c_uint64), ("reserved", C.c_uint64 * 1)]
 
 
 _lib = None
@@ -137,7 +137,7 @@ def qsac_get_stats(ctx) -> dict:
     if rc:
         raise QsacError(rc, "qsac_get_stats")
     return {n: int(getattr(st, n)) for n in ("steps", "reuse_heads", "miss_heads", "slot_hits", "slot_misses",
-                                             "resident_rows")}
+                                             "resident_rows", "guided_selects")}
 
 
 def qsac_get_stage_ms(ctx):

@@ -56,6 +56,19 @@ int attn_rows(int P, int k) {
   return (int)rows;
 }
 
+// Rank, within the select's sample of 4096 keys (one key in vpt), whose key bounds the candidates of the
+// guided select from below: the count C of keys at or above it has mean vpt * r and a standard deviation
+// below vpt * sqrt(r); r solves  vpt * (r - 6 sqrt(r)) = k, which puts k six deviations below the mean.
+// 0 (no guided select) when the candidates might not fit the list.
+int select_sample_rank(int k, int vpt) {
+  const double x = 3.0 + std::sqrt(9.0 + (double)k / vpt);
+  const int r = (int)std::ceil(x * x);
+  const double upper = (double)vpt * (r + 6.0 * std::sqrt((double)r));
+  // the bound is the lower edge of a histogram bin, which adds up to a bin's worth of keys: leave half the list
+  if (r > 2048 || upper > 0.5 * kSelectListCap) return 0;
+  return r;
+}
+
 void make_layout(const qsac_config* c, qsac_ws_layout* L) {
   const size_t P = (size_t)c->batch * c->n_kv_heads;
   const size_t G = (size_t)(c->n_q_heads / c->n_kv_heads);
@@ -171,25 +184,41 @@ void launch_score(const qsac_ctx* c, const qsac_step_args* a, u32* keys, u32* hi
   }
 }
 
+AttnArgs attn_args(const qsac_ctx* c, const qsac_step_args* a, const int* fetch_tok, const int* miss_count,
+                   float* part_ml, float* part_acc, int rows, int n_splits, int which) {
+  AttnArgs A;
+  A.q = static_cast<const uint16_t*>(a->q);
+  A.K_slots = static_cast<v4u*>(a->K_slots);
+  A.V_slots = static_cast<v4u*>(a->V_slots);
+  A.fetch_tok = fetch_tok;
+  A.miss_count = miss_count;
+  A.reuse_flags = a->reuse_flags;
+  A.part_ml = part_ml;
+  A.part_acc = part_acc;
+  A.out = a->out;
+  A.K_app = static_cast<const v4u*>(a->K_app);
+  A.V_app = static_cast<const v4u*>(a->V_app);
+  A.N = c->cfg.n_ctx;
+  A.n_app = a->n_app;
+  A.app_cap = c->cfg.append_capacity;
+  A.Hq = c->cfg.n_q_heads;
+  A.Hkv = c->cfg.n_kv_heads;
+  A.k = a->k;
+  A.k_max = c->cfg.k_max;
+  A.rows = rows;
+  A.n_splits = n_splits;
+  A.max_splits = c->L.max_splits;
+  A.which = which;
+  return A;
+}
+
 template <int DT, int G>
-void launch_attn(const qsac_ctx* c, const qsac_step_args* a, hipStream_t stream, dim3 grid, const FillSrc& src,
-                 const int* fetch_tok, const int* miss_count, float* part_ml, float* part_acc, int rows, int n_splits,
-                 int which) {
-  auto q = static_cast<const uint16_t*>(a->q);
-  auto Ks = static_cast<v4u*>(a->K_slots);
-  auto Vs = static_cast<v4u*>(a->V_slots);
+void launch_attn(const qsac_ctx* c, hipStream_t stream, const AttnArgs& A, const FillSrc& src) {
+  dim3 grid((unsigned)A.n_splits, (unsigned)c->P);
   if (c->fill_kernel)
-    qsac_attn_kernel<DT, G, false><<<grid, 256, 0, stream>>>(
-        q, Ks, Vs, src, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out,
-        static_cast<const v4u*>(a->K_app), static_cast<const v4u*>(a->V_app), a->n_app, c->cfg.append_capacity,
-        c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits,
-        which);
+    qsac_attn_kernel<DT, G, false><<<grid, 256, 0, stream>>>(A, src);
   else
-    qsac_attn_kernel<DT, G, true><<<grid, 256, 0, stream>>>(
-        q, Ks, Vs, src, fetch_tok, miss_count, a->reuse_flags, part_ml, part_acc, a->out,
-        static_cast<const v4u*>(a->K_app), static_cast<const v4u*>(a->V_app), a->n_app, c->cfg.append_capacity,
-        c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.n_ctx, a->k, c->cfg.k_max, rows, n_splits, c->L.max_splits,
-        which);
+    qsac_attn_kernel<DT, G, true><<<grid, 256, 0, stream>>>(A, src);
 }
 
 // Dispatch on (dtype, G) to the instantiated kernels.
@@ -297,6 +326,19 @@ int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
       return fail(QSAC_EHIP);
     }
   }
+  {
+    // the one-workgroup select keeps its candidate list in LDS beyond the default 64 KiB
+    const int lds_max = (int)(((size_t)(kSmallMaxN / 32) * 3 + 2 * (size_t)kSelectListCap) * sizeof(u32));
+    const void* fns[] = {(const void*)qsac_select_small_kernel<2, 1024>, (const void*)qsac_select_small_kernel<4, 1024>,
+                         (const void*)qsac_select_small_kernel<8, 1024>, (const void*)qsac_select_small_kernel<16, 1024>};
+    for (const void* fn : fns) {
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_max);
+      if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        return fail(QSAC_EHIP);
+      }
+    }
+  }
   rc = clear_state(c);
   if (rc != QSAC_OK) return fail(rc);
   *out = c;
@@ -397,13 +439,13 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   const int rows = attn_rows(P, k + a->n_app);
   const int n_splits = (k + a->n_app + rows - 1) / rows;
   dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
-  dim3 attn_grid((unsigned)n_splits, (unsigned)P);
   auto fill_on = [&](hipStream_t s) {
     qsac_fill_kernel<<<fill_grid, 256, 0, s>>>(miss_count, miss_slot, miss_tok, src, static_cast<v4u*>(a->K_slots),
                                                static_cast<v4u*>(a->V_slots), Hkv, N, k_max);
   };
   auto attend = [&](hipStream_t s, int which) {
-    QSAC_DISPATCH(launch_attn, c, a, s, attn_grid, src, fetch_tok, miss_count, part_ml, part_acc, rows, n_splits, which);
+    const AttnArgs A = attn_args(c, a, fetch_tok, miss_count, part_ml, part_acc, rows, n_splits, which);
+    QSAC_DISPATCH(launch_attn, c, s, A, src);
   };
   auto combine = [&]() {
     if (n_splits > 1)
@@ -430,18 +472,35 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   if (c->small) {
     // key vectors per thread that keep the pair's keys in registers
     const int64_t nvec = (N + 3) / 4;
-    const int bm_words = (int)((N + 63) / 64 * 2);
-    const size_t lds = (size_t)bm_words * 3 * sizeof(u32);
-#define QSAC_SELECT(VPT)                                                                                          \
-  qsac_select_small_kernel<VPT><<<P, kDiffThreads, lds, sm>>>(a->reuse_flags, keys, valid, a->slot_idx, set_sorted, \
-                                                             a->topk_idx, a->hit_mask, miss_count, miss_slot,      \
-                                                             miss_tok, fetch_tok, stats, src, Hkv, N, L.n_pad, k,  \
-                                                             k_max, bm_words)
-    if (nvec <= 2 * kDiffThreads) QSAC_SELECT(2);
-    else if (nvec <= 4 * kDiffThreads) QSAC_SELECT(4);
-    else if (nvec <= 8 * kDiffThreads) QSAC_SELECT(8);
-    else QSAC_SELECT(16);
-#undef QSAC_SELECT
+    const int vpt = nvec <= 2 * kDiffThreads ? 2 : nvec <= 4 * kDiffThreads ? 4 : nvec <= 8 * kDiffThreads ? 8 : 16;
+    SelArgs S;
+    S.reuse_flags = a->reuse_flags;
+    S.keys = keys;
+    S.valid = valid;
+    S.slot_idx = a->slot_idx;
+    S.set_sorted = set_sorted;
+    S.topk_idx = a->topk_idx;
+    S.hit_mask = a->hit_mask;
+    S.miss_count = miss_count;
+    S.miss_slot = miss_slot;
+    S.miss_tok = miss_tok;
+    S.fetch_tok = fetch_tok;
+    S.stats = stats;
+    S.N = N;
+    S.n_pad = (int64_t)L.n_pad;
+    S.Hkv = Hkv;
+    S.k = k;
+    S.k_max = k_max;
+    S.bm_words = (int)((N + 63) / 64 * 2);
+    S.list_cap = kSelectListCap;
+    S.r_sample = select_sample_rank(k, vpt);
+    const size_t lds_sel = ((size_t)S.bm_words * 3 + 2 * (size_t)kSelectListCap) * sizeof(u32);
+    switch (vpt) {
+      case 2: qsac_select_small_kernel<2, 1024><<<P, 1024, lds_sel, sm>>>(S, src); break;
+      case 4: qsac_select_small_kernel<4, 1024><<<P, 1024, lds_sel, sm>>>(S, src); break;
+      case 8: qsac_select_small_kernel<8, 1024><<<P, 1024, lds_sel, sm>>>(S, src); break;
+      default: qsac_select_small_kernel<16, 1024><<<P, 1024, lds_sel, sm>>>(S, src); break;
+    }
   } else {
     dim3 sel_grid((unsigned)(L.n_pad / kSelChunk), (unsigned)P);
     qsac_refine_kernel<1><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
@@ -499,6 +558,7 @@ int qsac_get_stats(qsac_ctx* c, qsac_stats* out) {
   out->slot_hits = dev[3];
   out->slot_misses = dev[4];
   out->resident_rows = dev[5];
+  out->guided_selects = dev[6];
   return QSAC_OK;
 }
 

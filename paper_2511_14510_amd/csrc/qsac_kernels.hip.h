@@ -40,6 +40,7 @@ constexpr int kTilePitch = 272;        // bytes between key rows of an LDS tile:
 constexpr int kSelChunk = 8192;    // keys per workgroup of the select passes
 constexpr int kFillRows = 64;      // miss-list entries per workgroup of the fill kernel
 constexpr int kDiffThreads = 1024;
+constexpr int kSelectListCap = 8192;   // candidates the guided select can hold in LDS (64 KiB of keys + indices)
 
 typedef __attribute__((ext_vector_type(2))) _Float16 half2_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf2_t;
@@ -841,39 +842,62 @@ __device__ __forceinline__ u32 or8(u32 v) {
   return v;
 }
 
-// Small-N path (N <= kSmallMaxN): one workgroup of 1024 threads per missing pair selects and
-// diffs in one go.  Three histogram passes (11 + 11 + 10 bits) pin the k-th largest key T
-// exactly; a fourth pass turns "key > T" and "key == T" into LDS bitmaps.  Thread t keeps key
-// vectors t, t + 1024, ... (VPT of them, 4 keys each) in registers, so the keys are read from
-// memory once.  Dynamic LDS: three bitmaps of bm_words words.
-template <int VPT>
-__global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
-    const uint8_t* __restrict__ reuse_flags, const u32* __restrict__ keys, u32* __restrict__ valid,
-    int* __restrict__ slot_idx, int* __restrict__ set_sorted, int* __restrict__ topk_idx,
-    uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count, int* __restrict__ miss_slot,
-    int* __restrict__ miss_tok, int* __restrict__ fetch_tok, u64* __restrict__ stats, FillSrc src, int Hkv,
-    int64_t N, int64_t n_pad, int k, int k_max, int bm_words) {
-  const int p = blockIdx.x;
-  if (reuse_flags[p]) return;
-  constexpr int NT = kDiffThreads;
+struct SelArgs {
+  const uint8_t* reuse_flags;
+  const u32* keys;
+  u32* valid;
+  int* slot_idx;
+  int* set_sorted;
+  int* topk_idx;
+  uint8_t* hit_mask;
+  int* miss_count;
+  int* miss_slot;
+  int* miss_tok;
+  int* fetch_tok;
+  u64* stats;
+  int64_t N, n_pad;
+  int Hkv, k, k_max, bm_words, list_cap, r_sample;
+};
+
+// Small-N path (N <= kSmallMaxN): one workgroup of NT threads per missing pair selects and diffs
+// in one go.  Thread t keeps key vectors t, t + NT, ... (VPT of them, 4 keys each) in registers,
+// so the keys are read from memory once.
+//
+// Full path: three histogram passes over all keys (11 + 11 + 10 bits) pin the k-th largest key
+// T exactly; a fourth pass turns "key > T" and "key == T" into LDS bitmaps.
+//
+// Guided path (r_sample > 0): a histogram of the top 12 key bits of 4 keys per thread (a 1/VPT
+// sample, spread over the context) gives a bound g, the lower edge of the bin that holds the
+// sample's r_sample-th largest key.  r_sample is chosen so that the number of keys >= g falls
+// between k and list_cap with near certainty.  k <= #{key >= g} proves T >= g, i.e. every key of
+// the top-k, and every key equal to T, is among those candidates: they are compacted into an
+// LDS list (a few per thread) and the three radix levels and the bitmaps run over the list
+// only.  If the count falls outside [k, list_cap] the full path runs; the result is the same
+// either way.
+//
+// Dynamic LDS (s_dyn): three bitmaps of bm_words words, then list_cap keys and list_cap indices.
+template <int VPT, int NT>
+__device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSrc& src, int p, u32* s_dyn) {
   constexpr int NV = VPT;
-  extern __shared__ u32 s_dyn[];
   __shared__ u32 s_hist[kHistCopies * kHistPitch];
   __shared__ int s_wave[32];
   __shared__ int s_res[2];
+  const int bm_words = A.bm_words, k = A.k, k_max = A.k_max;
   u32* s_new = s_dyn;
   u32* s_eq = s_dyn + bm_words;
   u32* s_old = s_dyn + 2 * bm_words;
+  u32* l_key = s_dyn + 3 * bm_words;
+  int* l_idx = reinterpret_cast<int*>(l_key + A.list_cap);
   const int tid = threadIdx.x;
-  u32* my_hist = s_hist + (tid & (kHistCopies - 1)) * kHistPitch;
-  const v4u* kp4 = reinterpret_cast<const v4u*>(keys + (size_t)p * n_pad);
-  const int n = (int)N;
+  const v4u* kp4 = reinterpret_cast<const v4u*>(A.keys + (size_t)p * A.n_pad);
+  const int n = (int)A.N;
   const int nvec = (n + 3) >> 2;  // n_pad is a multiple of 8192, so whole vectors can be read
   const int words = (n + 31) >> 5;
 
   // Keys at and past N read as 0 (the scoring kernel writes 0 there, vectors past the end are
   // zeroed here).  0 is below the key of every finite score, so it never reaches the k-th key's
-  // bin, never matches a prefix and never compares above or equal to T: no range checks below.
+  // bin, never matches a prefix and never compares above or equal to T or a bound: no range
+  // checks below.
   v4u kreg[NV];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
@@ -885,55 +909,128 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_select_small_kernel(
   int need = k, above;
   u32 prefix = 0;
   // level 0: bits 31..21; level 1: bits 20..10 under the level-0 bin; level 2: bits 9..0
-#pragma unroll
-  for (int level = 0; level < 3; ++level) {
-    const int shift = level == 1 ? 21 : 10;  // from level 1 on, key >> shift must equal prefix
-    const int sub = level == 0 ? 21 : (level == 1 ? 10 : 0);
-    const u32 mask = level == 2 ? 0x3ffu : 0x7ffu;
-    for (int i = tid; i < kHistCopies * kHistPitch; i += NT) s_hist[i] = 0;
+  auto level_shift = [](int level) { return level == 1 ? 21 : 10; };  // from level 1 on, key >> shift == prefix
+  auto level_sub = [](int level) { return level == 0 ? 21 : (level == 1 ? 10 : 0); };
+  auto level_mask = [](int level) { return level == 2 ? 0x3ffu : 0x7ffu; };
+
+  bool guided = false;  // uniform over the workgroup
+  int n_cand = 0, off = 0;
+  u32 bound = 0;
+  if (A.r_sample > 0) {
+    for (int i = tid; i < 4096; i += NT) s_hist[i] = 0;
     __syncthreads();
-    auto count = [&](const v4u kk) {
-      const u32 ks[4] = {kk.x, kk.y, kk.z, kk.w};
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool match = level == 0 || (ks[i] >> shift) == prefix;
-        if (match) atomicAdd(&my_hist[(ks[i] >> sub) & mask], 1u);
-      }
-    };
-#pragma unroll
-    for (int i = 0; i < NV; ++i) count(kreg[i]);
+    for (int j = 0; j < 4; ++j) {
+      const u32 key = NV >= 4 ? kreg[j * (NV / 4)].x : ((j & 1) ? kreg[(j >> 1) % NV].z : kreg[(j >> 1) % NV].x);
+      atomicAdd(&s_hist[key >> 20], 1u);
+    }
     __syncthreads();
-    const int nb = level == 2 ? 1024 : kBins;
-    const u32 b = (u32)find_bin<NT, kHistCopies>(s_hist, nb, need, &above, s_wave, s_res);
-    need -= above;
-    prefix = level == 0 ? b : (prefix << (level == 1 ? 11 : 10)) | b;
+    bound = (u32)find_bin<NT, 1>(s_hist, 4096, A.r_sample, &above, s_wave, s_res) << 20;
   }
-  const u32 T = prefix;  // the k-th largest key; `need` of the keys equal to it belong to the set
-  // bitmaps: a key vector is a nibble; 8 neighbouring lanes hold the 8 nibbles of one word
-  auto nibbles = [&](const v4u kk, const int v) {
-    const u32 ks[4] = {kk.x, kk.y, kk.z, kk.w};
-    u32 g = 0, q = 0;
+  if (bound != 0u) {
+    int cnt = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      g |= (u32)(ks[i] > T) << i;
-      q |= (u32)(ks[i] == T) << i;
-    }
-    const int sh = (v & 7) * 4;
-    g = or8(g << sh);
-    if (__ballot(q != 0)) q = or8(q << sh);  // uniform over the wave; keys equal to T are rare
-    if ((v & 7) == 0 && (v >> 3) < words) {
-      s_new[v >> 3] = g;
-      s_eq[v >> 3] = q;
-    }
-  };
+    for (int i = 0; i < NV; ++i)
+      cnt += (int)(kreg[i].x >= bound) + (int)(kreg[i].y >= bound) + (int)(kreg[i].z >= bound) +
+             (int)(kreg[i].w >= bound);
+    off = block_exclusive_scan<NT / 64>(cnt, s_wave, &n_cand);
+    guided = n_cand >= k && n_cand <= A.list_cap;
+  }
+  if (guided) {
+    // candidates into the list (its order is irrelevant: histograms and bitmaps do not depend on it)
 #pragma unroll
-  for (int i = 0; i < NV; ++i) nibbles(kreg[i], tid + i * NT);
+    for (int i = 0; i < NV; ++i) {
+      const u32 ks[4] = {kreg[i].x, kreg[i].y, kreg[i].z, kreg[i].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (ks[j] >= bound) {
+          l_key[off] = ks[j];
+          l_idx[off] = 4 * (tid + i * NT) + j;
+          ++off;
+        }
+    }
+    for (int i = tid; i < 2 * bm_words; i += NT) s_new[i] = 0;  // s_new and s_eq are adjacent
+#pragma unroll
+    for (int level = 0; level < 3; ++level) {
+      for (int i = tid; i < kBins; i += NT) s_hist[i] = 0;
+      __syncthreads();
+      for (int e = tid; e < n_cand; e += NT) {
+        const u32 key = l_key[e];
+        if (level == 0 || (key >> level_shift(level)) == prefix)
+          atomicAdd(&s_hist[(key >> level_sub(level)) & level_mask(level)], 1u);
+      }
+      __syncthreads();
+      const u32 bsel = (u32)find_bin<NT, 1>(s_hist, level == 2 ? 1024 : kBins, need, &above, s_wave, s_res);
+      need -= above;
+      prefix = level == 0 ? bsel : (prefix << (level == 1 ? 11 : 10)) | bsel;
+    }
+    const u32 T = prefix;
+    for (int e = tid; e < n_cand; e += NT) {
+      const u32 key = l_key[e];
+      const int idx = l_idx[e];
+      if (key > T)
+        atomicOr(&s_new[idx >> 5], 1u << (idx & 31));
+      else if (key == T)
+        atomicOr(&s_eq[idx >> 5], 1u << (idx & 31));
+    }
+  } else {
+    u32* my_hist = s_hist + (tid & (kHistCopies - 1)) * kHistPitch;
+#pragma unroll
+    for (int level = 0; level < 3; ++level) {
+      for (int i = tid; i < kHistCopies * kHistPitch; i += NT) s_hist[i] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const u32 ks[4] = {kreg[i].x, kreg[i].y, kreg[i].z, kreg[i].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (level == 0 || (ks[j] >> level_shift(level)) == prefix)
+            atomicAdd(&my_hist[(ks[j] >> level_sub(level)) & level_mask(level)], 1u);
+      }
+      __syncthreads();
+      const u32 bsel =
+          (u32)find_bin<NT, kHistCopies>(s_hist, level == 2 ? 1024 : kBins, need, &above, s_wave, s_res);
+      need -= above;
+      prefix = level == 0 ? bsel : (prefix << (level == 1 ? 11 : 10)) | bsel;
+    }
+    const u32 T = prefix;
+    // bitmaps: a key vector is a nibble; 8 neighbouring lanes hold the 8 nibbles of one word
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int v = tid + i * NT;
+      const u32 ks[4] = {kreg[i].x, kreg[i].y, kreg[i].z, kreg[i].w};
+      u32 g = 0, q = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        g |= (u32)(ks[j] > T) << j;
+        q |= (u32)(ks[j] == T) << j;
+      }
+      const int sh = (v & 7) * 4;
+      g = or8(g << sh);
+      if (__ballot(q != 0)) q = or8(q << sh);  // uniform over the wave; keys equal to T are rare
+      if ((v & 7) == 0 && (v >> 3) < words) {
+        s_new[v >> 3] = g;
+        s_eq[v >> 3] = q;
+      }
+    }
+  }
+  // prefix: the k-th largest key; `need` of the keys equal to it belong to the set
+  if (tid == 0 && guided) atomicAdd(&A.stats[6], 1ull);
   __syncthreads();
-  // 65536 keys = 2048 words = 2 per lane
-  diff_phases<NT, 2>(s_new, s_eq, s_old, valid[p] != 0, need, words, k, slot_idx + (size_t)p * k_max,
-                  set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
-                  miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max, fetch_tok + (size_t)p * k_max,
-                  miss_count + p, valid + p, stats, src.slot[p % Hkv] >= 0, s_wave);
+  // 65536 keys = 2048 bitmap words
+  diff_phases<NT, 2048 / NT>(s_new, s_eq, s_old, A.valid[p] != 0, need, words, k, A.slot_idx + (size_t)p * k_max,
+                             A.set_sorted + (size_t)p * k_max, A.topk_idx + (size_t)p * k, A.hit_mask + (size_t)p * k,
+                             A.miss_slot + (size_t)p * k_max, A.miss_tok + (size_t)p * k_max,
+                             A.fetch_tok + (size_t)p * k_max, A.miss_count + p, A.valid + p, A.stats,
+                             src.slot[p % A.Hkv] >= 0, s_wave);
+}
+
+template <int VPT, int NT>
+__global__ __launch_bounds__(NT) void qsac_select_small_kernel(SelArgs A, FillSrc src) {
+  extern __shared__ u32 s_dyn[];
+  const int p = blockIdx.x;
+  if (A.reuse_flags[p]) return;
+  select_small_body<VPT, NT>(A, src, p, s_dyn);
 }
 
 // ---------------------------------------------------------------- fill
@@ -1016,22 +1113,52 @@ __device__ __forceinline__ float row16_max(float v) {
   return v;
 }
 
-template <int DT, int G, bool FETCH>
-__global__ __launch_bounds__(256) void qsac_attn_kernel(
-    const uint16_t* __restrict__ q, v4u* __restrict__ K_slots, v4u* __restrict__ V_slots, FillSrc src,
-    const int* __restrict__ fetch_tok,
-    const int* __restrict__ miss_count, const uint8_t* __restrict__ reuse_flags, float* __restrict__ part_ml,
-    float* __restrict__ part_acc, float* __restrict__ out, const v4u* __restrict__ K_app,
-    const v4u* __restrict__ V_app, int n_app, int app_cap, int Hq, int Hkv, int64_t N, int k, int k_max, int rows,
-    int n_splits, int max_splits, int which) {
-  const int p = blockIdx.y, split = blockIdx.x;
-  if (!pair_selected(which, reuse_flags, p)) return;
-  constexpr int GP = G > 4 ? 8 : 4;  // queries padded to whole lane quarters
-  __shared__ __attribute__((aligned(16))) unsigned char s_tile[4][16 * kTilePitch];
-  __shared__ __attribute__((aligned(16))) float s_p[4][16][GP];
-  __shared__ __attribute__((aligned(16))) float s_alpha[4][GP];
-  __shared__ float s_ml[4][G][2];
-  __shared__ float s_acc[4][G][kD];
+struct AttnArgs {
+  const uint16_t* q;
+  v4u* K_slots;
+  v4u* V_slots;
+  const int* fetch_tok;
+  const int* miss_count;
+  const uint8_t* reuse_flags;
+  float* part_ml;
+  float* part_acc;
+  float* out;
+  const v4u* K_app;
+  const v4u* V_app;
+  int64_t N;
+  int n_app, app_cap, Hq, Hkv, k, k_max, rows, n_splits, max_splits, which;
+};
+
+// LDS of one attention workgroup of NW waves
+template <int G, int NW>
+struct AttnLds {
+  static constexpr int GP = G > 4 ? 8 : 4;  // queries padded to whole lane quarters
+  alignas(16) unsigned char tile[NW][16 * kTilePitch];
+  alignas(16) float p[NW][16][GP];
+  alignas(16) float alpha[NW][GP];
+  float ml[NW][G][2];
+  float acc[NW][G][kD];
+};
+
+// The work of one attention workgroup of NW waves (all of its threads call this).
+template <int DT, int G, bool FETCH, int NW>
+__device__ __forceinline__ void attn_body(const AttnArgs& A, const FillSrc& src, int p, int split,
+                                          AttnLds<G, NW>& S) {
+  constexpr int GP = AttnLds<G, NW>::GP;
+  constexpr int kStep = NW * 16;  // slots between two tiles of a wave
+  const uint16_t* __restrict__ q = A.q;
+  v4u* __restrict__ K_slots = A.K_slots;
+  v4u* __restrict__ V_slots = A.V_slots;
+  const int* __restrict__ fetch_tok = A.fetch_tok;
+  const int* __restrict__ miss_count = A.miss_count;
+  float* __restrict__ part_ml = A.part_ml;
+  float* __restrict__ part_acc = A.part_acc;
+  float* __restrict__ out = A.out;
+  const v4u* __restrict__ K_app = A.K_app;
+  const v4u* __restrict__ V_app = A.V_app;
+  const int64_t N = A.N;
+  const int n_app = A.n_app, app_cap = A.app_cap, Hq = A.Hq, Hkv = A.Hkv, k = A.k, k_max = A.k_max, rows = A.rows,
+            n_splits = A.n_splits, max_splits = A.max_splits;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = lane & 15, quarter = lane >> 4;
   const int b = p / Hkv, h = p % Hkv;
@@ -1101,13 +1228,13 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
   };
   // K tile -> LDS -> logits -> online softmax -> weights and rescale factors in LDS
   auto stage_k = [&](const v4u (&kk)[4]) {
-    unsigned char* tile = s_tile[wave];
+    unsigned char* tile = S.tile[wave];
 #pragma unroll
     for (int j = 0; j < 4; ++j) *reinterpret_cast<v4u*>(tile + (4 * j + quarter) * kTilePitch + m * 16) = kk[j];
     __builtin_amdgcn_wave_barrier();
   };
   auto softmax_tile = [&](int t0) {
-    const unsigned char* tile = s_tile[wave];
+    const unsigned char* tile = S.tile[wave];
     f4_t sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -1127,16 +1254,16 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
       mrun[i] = mnew;
     }
     if (quarter * 4 < GP) {
-      *reinterpret_cast<f4_t*>(&s_p[wave][m][quarter * 4]) = pw;
-      if (m == 0) *reinterpret_cast<f4_t*>(&s_alpha[wave][quarter * 4]) = al;
+      *reinterpret_cast<f4_t*>(&S.p[wave][m][quarter * 4]) = pw;
+      if (m == 0) *reinterpret_cast<f4_t*>(&S.alpha[wave][quarter * 4]) = al;
     }
     __builtin_amdgcn_wave_barrier();
   };
   // acc <- acc * alpha + sum over this lane's four rows of weight * V row
   auto fold_v = [&](const v4u (&vv)[4]) {
     float a[GP];
-    *reinterpret_cast<f4_t*>(&a[0]) = *reinterpret_cast<const f4_t*>(&s_alpha[wave][0]);
-    if (GP > 4) *reinterpret_cast<f4_t*>(&a[4]) = *reinterpret_cast<const f4_t*>(&s_alpha[wave][4]);
+    *reinterpret_cast<f4_t*>(&a[0]) = *reinterpret_cast<const f4_t*>(&S.alpha[wave][0]);
+    if (GP > 4) *reinterpret_cast<f4_t*>(&a[4]) = *reinterpret_cast<const f4_t*>(&S.alpha[wave][4]);
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -1144,8 +1271,8 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       float pr[GP];
-      *reinterpret_cast<f4_t*>(&pr[0]) = *reinterpret_cast<const f4_t*>(&s_p[wave][4 * j + quarter][0]);
-      if (GP > 4) *reinterpret_cast<f4_t*>(&pr[4]) = *reinterpret_cast<const f4_t*>(&s_p[wave][4 * j + quarter][4]);
+      *reinterpret_cast<f4_t*>(&pr[0]) = *reinterpret_cast<const f4_t*>(&S.p[wave][4 * j + quarter][0]);
+      if (GP > 4) *reinterpret_cast<f4_t*>(&pr[4]) = *reinterpret_cast<const f4_t*>(&S.p[wave][4 * j + quarter][4]);
       const u32 w[4] = {vv[j].x, vv[j].y, vv[j].z, vv[j].w};
       float vf[8];
 #pragma unroll
@@ -1172,21 +1299,21 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
       load_tok(t0, tokC);
       load_tile(t0, tokC, kk, Kp, Ks, Ka);
       load_tile(t0, tokC, vv, Vp, Vs, Va);
-      if (t0 + 64 < s_end) load_tok(t0 + 64, tokN);
+      if (t0 + kStep < s_end) load_tok(t0 + kStep, tokN);
     }
-    for (; t0 < s_end; t0 += 64) {
-      const bool more = t0 + 64 < s_end;
+    for (; t0 < s_end; t0 += kStep) {
+      const bool more = t0 + kStep < s_end;
       store_fetched(t0, tokC, kk, Kp);
       stage_k(kk);
-      if (more) load_tile(t0 + 64, tokN, kk, Kp, Ks, Ka);
+      if (more) load_tile(t0 + kStep, tokN, kk, Kp, Ks, Ka);
       softmax_tile(t0);
       store_fetched(t0, tokC, vv, Vp);
       fold_v(vv);
       if (more) {
-        load_tile(t0 + 64, tokN, vv, Vp, Vs, Va);
+        load_tile(t0 + kStep, tokN, vv, Vp, Vs, Va);
 #pragma unroll
         for (int j = 0; j < 4; ++j) tokC[j] = tokN[j];
-        if (t0 + 128 < s_end) load_tok(t0 + 128, tokN);
+        if (t0 + 2 * kStep < s_end) load_tok(t0 + 2 * kStep, tokN);
       }
     }
   }
@@ -1208,8 +1335,8 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
     for (int i = 0; i < 4; ++i) {
       const int g = quarter * 4 + i;
       if (g < G) {
-        s_ml[wave][g][0] = mrun[i];
-        s_ml[wave][g][1] = lrun[i];
+        S.ml[wave][g][0] = mrun[i];
+        S.ml[wave][g][1] = lrun[i];
       }
     }
   }
@@ -1217,23 +1344,23 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int d = 0; d < 8; ++d) s_acc[wave][g][m * 8 + d] = acc[g][d];
+      for (int d = 0; d < 8; ++d) S.acc[wave][g][m * 8 + d] = acc[g][d];
   }
   __syncthreads();
   const int b_out = p / Hkv, h_out = p % Hkv;
   float* out_p = out + ((size_t)b_out * Hq + (size_t)h_out * G) * kD;
-  for (int i = threadIdx.x; i < G * kD; i += 256) {
+  for (int i = threadIdx.x; i < G * kD; i += NW * 64) {
     const int g = i >> 7, d = i & 127;
     float M = kNegInf;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, s_ml[w][g][0]);
+    for (int w = 0; w < NW; ++w) M = fmaxf(M, S.ml[w][g][0]);
     float L = 0.f, A = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float mw = s_ml[w][g][0];
+    for (int w = 0; w < NW; ++w) {
+      const float mw = S.ml[w][g][0];
       const float wt = (mw == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-      L += s_ml[w][g][1] * wt;
-      A += s_acc[w][g][d] * wt;
+      L += S.ml[w][g][1] * wt;
+      A += S.acc[w][g][d] * wt;
     }
     if (n_splits == 1) {
       out_p[i] = A / L;
@@ -1246,6 +1373,14 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(
       }
     }
   }
+}
+
+template <int DT, int G, bool FETCH>
+__global__ __launch_bounds__(256) void qsac_attn_kernel(AttnArgs A, FillSrc src) {
+  const int p = blockIdx.y, split = blockIdx.x;
+  if (!pair_selected(A.which, A.reuse_flags, p)) return;
+  __shared__ AttnLds<G, 4> S;
+  attn_body<DT, G, FETCH, 4>(A, src, p, split, S);
 }
 
 // One workgroup of 128 threads per query head: merges the attention splits and normalises.

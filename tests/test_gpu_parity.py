@@ -55,7 +55,8 @@ def test_ragged_shapes_gqa5_bf16(H, flags):
 @pytest.mark.parametrize("G,dtype", [(1, "f16"), (2, "bf16"), (3, "f16"), (4, "bf16"), (6, "bf16"), (7, "f16"), (8, "bf16")])
 @pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_SCORE_VALU])
 def test_group_sizes(H, G, dtype, flags):
-    run_chain(H, B=1, Hq=2 * G, Hkv=2, N=2500, k=130, k_max=130, dtype=dtype, steps=10, flags=flags, seed=10 + G)
+    run_chain(H, B=1, Hq=2 * G, Hkv=2, N=2500, k=130, k_max=130, dtype=dtype, steps=10, flags=flags, seed=10 + G,
+              side_stream=False)
 
 
 @pytest.mark.parametrize("N,k", [(1, 1), (3, 3), (17, 1), (64, 64), (100, 99), (1024, 1), (1025, 1025)])
@@ -325,3 +326,11 @@ def test_back_to_back_steps_without_host_sync(H):
     for x, y in zip(res[0][:5], res[1][:5]):
         assert torch.equal(x, y)
     assert res[0][5] == res[1][5]
+
+
+@pytest.mark.parametrize("N,k,k_max", [(9001, 300, 333), (40000, 1111, 1200), (65536, 2048, 2048), (700, 700, 700),
+                                       (3000, 16, 16), (65536, 5000, 5000)])
+def test_guided_select(H, N, k, k_max):
+    """The one-workgroup select takes its top-k from the keys above a sampled bound when it can, and from all
+    keys when it cannot (k = N, k too large for the candidate list): sets, masks and slots against the oracle."""
+    par = run_chain(H, B=3, Hq=8, Hkv=2, N=N, k=k, k_max=k_max, dtype="bf16", steps=12, seed=77, side_stream=False)
