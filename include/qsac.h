@@ -110,7 +110,9 @@ typedef struct {
   size_t part_acc;   /* f32 [P][G][splits][128] unnormalised partial outputs                              */
   size_t stats;      /* u64 [8]              cumulative counters                                          */
   size_t importance; /* f64 [n_q_heads]      Eq. (2) weights                                              */
-  size_t sel_r;      /* i32 [P]              keys equal to the k-th key that belong to the set (last miss)        */
+  size_t sel_r;      /* i32 [P][8]           per pair: keys equal to the k-th key that belong to the set, then the
+                                             threshold bins found so far by the grid-wide select (last miss)      */
+  size_t chunk_cnt;  /* i32 [P][n_pad/8192][2] set bits per 8192-key chunk of bm_new and bm_eq (long contexts)    */
   size_t fetch_tok;  /* i32 [P][k_max]       per slot: token whose rows the slot still has to receive, or -1      */
   size_t total;      /* bytes needed                                                                      */
   int64_t n_pad;     /* N rounded up to the select chunk                                                  */

@@ -37,7 +37,7 @@ class qsac_config(C.Structure):
 class qsac_ws_layout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
                 ("valid", "set_sorted", "keys", "hist", "bm_new", "bm_eq", "bm_old", "miss_count", "miss_slot",
-                 "miss_tok", "part_ml", "part_acc", "stats", "importance", "sel_r", "fetch_tok", "total")] + \
+                 "miss_tok", "part_ml", "part_acc", "stats", "importance", "sel_r", "chunk_cnt", "fetch_tok", "total")] + \
                [("n_pad", C.c_int64), ("words", C.c_int32), ("max_splits", C.c_int32)]
 
 

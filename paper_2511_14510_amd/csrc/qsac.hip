@@ -95,7 +95,8 @@ void make_layout(const qsac_config* c, qsac_ws_layout* L) {
   L->part_acc = take(P * G * splits * kD * 4);
   L->stats = take(8 * 8);
   L->importance = take((size_t)c->n_q_heads * 8);
-  L->sel_r = take(P * 4);
+  L->sel_r = take(P * kSelStride * 4);
+  L->chunk_cnt = take(P * (n_pad / kSelChunk) * 2 * 4);
   L->fetch_tok = take(P * c->k_max * 4);
   L->total = off;
   L->n_pad = (int64_t)n_pad;
@@ -328,9 +329,12 @@ int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
   }
   {
     // the one-workgroup select keeps its candidate list in LDS beyond the default 64 KiB
-    const int lds_max = (int)(((size_t)(kSmallMaxN / 32) * 3 + 2 * (size_t)kSelectListCap) * sizeof(u32));
+    // (and the long-context diff its lists)
+    const int lds_max = std::max((int)(((size_t)(kSmallMaxN / 32) * 3 + 2 * (size_t)kSelectListCap) * sizeof(u32)),
+                                 kDiffListMax * 13);
     const void* fns[] = {(const void*)qsac_select_small_kernel<2, 1024>, (const void*)qsac_select_small_kernel<4, 1024>,
-                         (const void*)qsac_select_small_kernel<8, 1024>, (const void*)qsac_select_small_kernel<16, 1024>};
+                         (const void*)qsac_select_small_kernel<8, 1024>, (const void*)qsac_select_small_kernel<16, 1024>,
+                         (const void*)qsac_diff_list_kernel};
     for (const void* fn : fns) {
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_max);
       if (e != hipSuccess) {
@@ -503,18 +507,31 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     }
   } else {
     dim3 sel_grid((unsigned)(L.n_pad / kSelChunk), (unsigned)P);
-    qsac_refine_kernel<1><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
-    qsac_refine_kernel<2><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, N, L.n_pad, k);
-    qsac_mark_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, bm_new, bm_eq, bm_old, sel_r, N, L.n_pad,
-                                              L.words, k);
-    // bitmap words per lane of the 1024-thread diff: 8 up to 262144 keys, 32 up to 2^20
+    qsac_refine_kernel<1><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, sel_r, N, L.n_pad, k);
+    qsac_refine_kernel<2><<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, sel_r, N, L.n_pad, k);
+    if (L.words > 8 * kDiffThreads && k <= kDiffListMax) {
+      // Long contexts: the set becomes a token list written by the whole grid, and the one-workgroup diff works on
+      // that list in LDS (one workgroup alone takes tens of microseconds to read bitmaps of this size).
+      int* chunk_cnt = reinterpret_cast<int*>(ws + L.chunk_cnt);
+      qsac_mark_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, bm_new, bm_eq, bm_old, sel_r, chunk_cnt, N,
+                                                L.n_pad, L.words, k);
+      qsac_emit_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, bm_new, bm_eq, chunk_cnt, sel_r, set_sorted,
+                                                a->topk_idx, L.words, k, k_max);
+      qsac_diff_list_kernel<<<P, kDiffThreads, (size_t)k * 13, sm>>>(a->reuse_flags, valid, a->slot_idx, set_sorted,
+                                                                    a->hit_mask, miss_count, miss_slot, miss_tok,
+                                                                    fetch_tok, stats, src, Hkv, k, k_max);
+    } else {
+      qsac_mark_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, bm_new, bm_eq, bm_old, sel_r, nullptr, N,
+                                                L.n_pad, L.words, k);
+      // bitmap words per lane of the 1024-thread diff: 8 up to 262144 keys, 32 up to 2^20
 #define QSAC_DIFF(WPL)                                                                                             \
   qsac_diff_kernel<WPL><<<P, kDiffThreads, 0, sm>>>(a->reuse_flags, valid, bm_new, bm_eq, bm_old, sel_r, a->slot_idx, \
                                                    set_sorted, a->topk_idx, a->hit_mask, miss_count, miss_slot,     \
                                                    miss_tok, fetch_tok, stats, src, Hkv, L.words, k, k_max)
-    if (L.words <= 8 * kDiffThreads) QSAC_DIFF(8);
-    else QSAC_DIFF(32);
+      if (L.words <= 8 * kDiffThreads) QSAC_DIFF(8);
+      else QSAC_DIFF(32);
 #undef QSAC_DIFF
+    }
   }
   // 4. fill the missing rows (own kernel, or folded into the attention kernel's loads); 5. attention
   if (side_attn) {

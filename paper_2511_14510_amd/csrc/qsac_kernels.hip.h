@@ -529,26 +529,43 @@ __global__ __launch_bounds__(256) void qsac_score_valu_kernel(
 
 // LEVEL 1: histogram bits 20..10 of the keys whose bits 31..21 equal the level-0 threshold bin.
 // LEVEL 2: histogram bits 9..0 of the keys whose bits 31..10 equal the two-level prefix.
-// Every workgroup re-derives the prefix from the finished histograms of the levels above
-// (2048 counters, read from L2) instead of waiting for a separate one-workgroup kernel.
+// Every workgroup derives the threshold bin of the level above from that level's finished
+// histogram (2048 counters, read from L2) instead of waiting for a separate one-workgroup
+// kernel; the first workgroup of a pair leaves it in sel (kSelStride ints per pair: r, bin 0,
+// rest after bin 0, bin 1, rest after bin 1) for the kernels that follow.
+constexpr int kSelStride = 8;
 template <int LEVEL>
 __global__ __launch_bounds__(256) void qsac_refine_kernel(const uint8_t* __restrict__ reuse_flags,
                                                           const u32* __restrict__ keys, u32* __restrict__ hist,
-                                                          int64_t N, int64_t n_pad, int k) {
+                                                          int* __restrict__ sel, int64_t N, int64_t n_pad, int k) {
   const int p = blockIdx.y;
   if (reuse_flags[p]) return;
   __shared__ u32 s_hist[kBins];
   __shared__ int s_wave[5];
   __shared__ int s_res[2];
   u32* hp = hist + (size_t)p * 3 * kBins;
+  int* sp = sel + (size_t)p * kSelStride;
   for (int i = threadIdx.x; i < kBins; i += 256) s_hist[i] = 0;
   int above;
   int need = k;
-  u32 prefix = (u32)find_bin<256>(hp, kBins, need, &above, s_wave, s_res);
-  need -= above;
+  u32 prefix;
   int shift = 21;
-  if (LEVEL == 2) {
+  if (LEVEL == 1) {
+    prefix = (u32)find_bin<256>(hp, kBins, need, &above, s_wave, s_res);
+    need -= above;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      sp[1] = (int)prefix;
+      sp[2] = need;
+    }
+  } else {
+    prefix = (u32)sp[1];
+    need = sp[2];
     u32 b1 = (u32)find_bin<256>(hp + kBins, kBins, need, &above, s_wave, s_res);
+    need -= above;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      sp[3] = (int)b1;
+      sp[4] = need;
+    }
     prefix = (prefix << 11) | b1;
     shift = 10;
   }
@@ -575,26 +592,28 @@ __global__ __launch_bounds__(256) void qsac_refine_kernel(const uint8_t* __restr
 }
 
 // With the k-th largest key T known exactly: bitmap of keys > T, bitmap of keys == T (64 keys
-// per wave-wide ballot), and a cleared bitmap for the cached tokens.
+// per wave-wide ballot), and either a cleared bitmap for the cached tokens (for qsac_diff_kernel)
+// or the chunk's two bit counts (chunk_cnt given: for qsac_emit_kernel).
 __global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restrict__ reuse_flags,
                                                         const u32* __restrict__ keys, const u32* __restrict__ hist,
                                                         u32* __restrict__ bm_new, u32* __restrict__ bm_eq,
-                                                        u32* __restrict__ bm_old, int* __restrict__ sel_r,
-                                                        int64_t N, int64_t n_pad, int words, int k) {
+                                                        u32* __restrict__ bm_old, int* __restrict__ sel,
+                                                        int* __restrict__ chunk_cnt, int64_t N, int64_t n_pad,
+                                                        int words, int k) {
   const int p = blockIdx.y;
   if (reuse_flags[p]) return;
   __shared__ int s_wave[5];
   __shared__ int s_res[2];
+  __shared__ int s_cnt[2];
+  if (threadIdx.x < 2) s_cnt[threadIdx.x] = 0;  // find_bin's barriers come before its use
   const u32* hp = hist + (size_t)p * 3 * kBins;
-  int above, need = k;
-  u32 b0 = (u32)find_bin<256>(hp, kBins, need, &above, s_wave, s_res);
-  need -= above;
-  u32 b1 = (u32)find_bin<256>(hp + kBins, kBins, need, &above, s_wave, s_res);
-  need -= above;
+  int* sp = sel + (size_t)p * kSelStride;
+  const u32 b0 = (u32)sp[1], b1 = (u32)sp[3];
+  int above, need = sp[4];
   u32 b2 = (u32)find_bin<256>(hp + 2 * kBins, 1024, need, &above, s_wave, s_res);
   need -= above;  // number of keys equal to T that belong to the set (>= 1)
   const u32 T = (b0 << 21) | (b1 << 10) | b2;
-  if (blockIdx.x == 0 && threadIdx.x == 0) sel_r[p] = need;
+  if (blockIdx.x == 0 && threadIdx.x == 0) sp[0] = need;
 
   const int lane = threadIdx.x & 63;
   const int64_t base = (int64_t)blockIdx.x * kSelChunk;
@@ -602,6 +621,8 @@ __global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restric
   u32* gt = bm_new + (size_t)p * words;
   u32* eq = bm_eq + (size_t)p * words;
   u32* old = bm_old + (size_t)p * words;
+  const bool clear_old = chunk_cnt == nullptr;
+  int cg = 0, ce = 0;  // lane 0: bits of this wave
 #pragma unroll 4
   for (int i = 0; i < kSelChunk / 256; ++i) {
     const int64_t n = base + (int64_t)i * 256 + threadIdx.x;
@@ -609,16 +630,208 @@ __global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restric
     const bool in = n < N;
     const u64 mg = __ballot(in && key > T);
     const u64 me = __ballot(in && key == T);
+    cg += __popcll(mg);
+    ce += __popcll(me);
     const int64_t w = n >> 5;  // lane 0 -> low word, lane 32 -> high word of this wave's 64 keys
     if (lane == 0) {
       gt[w] = (u32)mg;
       eq[w] = (u32)me;
-      old[w] = 0;
+      if (clear_old) old[w] = 0;
     } else if (lane == 32) {
       gt[w] = (u32)(mg >> 32);
       eq[w] = (u32)(me >> 32);
-      old[w] = 0;
+      if (clear_old) old[w] = 0;
     }
+  }
+  if (!clear_old) {
+    if (lane == 0) {
+      atomicAdd(&s_cnt[0], cg);
+      atomicAdd(&s_cnt[1], ce);
+    }
+    __syncthreads();
+    if (threadIdx.x < 2) chunk_cnt[((size_t)p * gridDim.x + blockIdx.x) * 2 + threadIdx.x] = s_cnt[threadIdx.x];
+  }
+}
+
+// Long contexts (more bitmap words than one workgroup reads quickly): the selected set as an
+// ascending token list, written by the whole grid.  Workgroup (chunk, pair) of 256 threads, one
+// bitmap word each: the chunks' bit counts (qsac_mark_kernel) give the number of selected tokens
+// before the chunk; of the keys equal to the k-th key, the r with the lowest indices overall
+// are selected, i.e. those whose rank among the equal keys is below r.  The list goes to
+// set_sorted and topk_idx.
+__global__ __launch_bounds__(256) void qsac_emit_kernel(const uint8_t* __restrict__ reuse_flags,
+                                                        const u32* __restrict__ bm_new,
+                                                        const u32* __restrict__ bm_eq,
+                                                        const int* __restrict__ chunk_cnt,
+                                                        const int* __restrict__ sel, int* __restrict__ set_sorted,
+                                                        int* __restrict__ topk_idx, int words, int k, int k_max) {
+  const int p = blockIdx.y, c = blockIdx.x, n_chunks = gridDim.x;
+  if (reuse_flags[p]) return;
+  __shared__ int s_wave[5];
+  const int tid = threadIdx.x;
+  const int r = sel[(size_t)p * kSelStride];
+  const int* cnt = chunk_cnt + (size_t)p * n_chunks * 2;
+  // bits of the chunks before this one
+  int g_before = 0, e_before = 0;
+  for (int cc = tid; cc < c; cc += 256) {
+    g_before += cnt[2 * cc];
+    e_before += cnt[2 * cc + 1];
+  }
+  int total;
+  (void)block_exclusive_scan<4>(g_before, s_wave, &total);
+  g_before = total;
+  (void)block_exclusive_scan<4>(e_before, s_wave, &total);
+  e_before = total;
+  const int w = c * (kSelChunk / 32) + tid;  // words is a multiple of kSelChunk / 32
+  u32 bits = bm_new[(size_t)p * words + w];
+  if (cnt[2 * c + 1] > 0) {  // uniform: keys equal to the k-th key in this chunk
+    u32 e = bm_eq[(size_t)p * words + w];
+    const int ce = __popc(e);
+    const int rank = e_before + block_exclusive_scan<4>(ce, s_wave, &total);  // equal keys at lower indices
+    if (ce && rank + ce > r) {  // keep only the lowest (r - rank) bits of e
+      int keep = r - rank;
+      u32 kept = 0;
+      while (keep > 0 && e) {
+        const u32 low = e & (0u - e);
+        kept |= low;
+        e ^= low;
+        --keep;
+      }
+      e = kept;
+    }
+    bits |= e;
+  }
+  int pos = g_before + min(r, e_before) + block_exclusive_scan<4>(__popc(bits), s_wave, &total);
+  int* ss = set_sorted + (size_t)p * k_max;
+  int* tk = topk_idx + (size_t)p * k;
+  while (bits) {
+    const int bit = __ffs(bits) - 1;
+    bits &= bits - 1;
+    if (pos < k) {  // the set has exactly k members; the guard only protects the buffers
+      ss[pos] = w * 32 + bit;
+      tk[pos] = w * 32 + bit;
+    }
+    ++pos;
+  }
+}
+
+// The diff for qsac_emit_kernel's list (k <= kDiffListMax): one workgroup of 1024 threads per
+// missing pair, with everything a lookup touches in LDS:
+//  1. the ascending list of the set into LDS (l_new);
+//  2. every cached token (slot_idx) is looked up in l_new by binary search: found marks the list
+//     entry as a hit, not found marks the slot for eviction;
+//  3. hit mask, ascending list of tokens to fetch (entries that are no hit), ascending list of
+//     evicted slots;
+//  4. the i-th evicted slot takes the i-th token to fetch.
+// Dynamic LDS: l_new, l_mt, l_ms (k ints each), l_hit (k bytes).
+constexpr int kDiffListMax = 8192;
+__global__ __launch_bounds__(kDiffThreads) void qsac_diff_list_kernel(
+    const uint8_t* __restrict__ reuse_flags, u32* __restrict__ valid, int* __restrict__ slot_idx,
+    const int* __restrict__ set_sorted, uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count,
+    int* __restrict__ miss_slot, int* __restrict__ miss_tok, int* __restrict__ fetch_tok, u64* __restrict__ stats,
+    FillSrc src, int Hkv, int k, int k_max) {
+  const int p = blockIdx.x;
+  if (reuse_flags[p]) return;
+  constexpr int NT = kDiffThreads;
+  constexpr int kMaxSpt = kDiffListMax / NT;
+  extern __shared__ int s_lists[];
+  __shared__ int s_wave[32];
+  int* l_new = s_lists;
+  int* l_mt = l_new + k;
+  int* l_ms = l_mt + k;
+  uint8_t* l_hit = reinterpret_cast<uint8_t*>(l_ms + k);
+  const int tid = threadIdx.x;
+  int* sl = slot_idx + (size_t)p * k_max;
+  const int* ss = set_sorted + (size_t)p * k_max;
+  uint8_t* hm = hit_mask + (size_t)p * k;
+  int* ms = miss_slot + (size_t)p * k_max;
+  int* mt = miss_tok + (size_t)p * k_max;
+  int* ft = fetch_tok + (size_t)p * k_max;
+  const bool was_valid = valid[p] != 0;
+  // the thread's slots (and, in 3, its entries of the list): [j0, j1), at most kMaxSpt
+  const int spt = (k + NT - 1) / NT;
+  const int j0 = min(tid * spt, k), j1 = min(j0 + spt, k);
+  int mytok[kMaxSpt];
+#pragma unroll
+  for (int i = 0; i < kMaxSpt; ++i) mytok[i] = (was_valid && j0 + i < j1) ? sl[j0 + i] : -1;
+  // 1
+  for (int j = tid; j < k; j += NT) {
+    l_new[j] = ss[j];
+    l_hit[j] = 0;
+    ft[j] = -1;  // slots that keep their row; 4 names the others
+  }
+  __syncthreads();
+  // 2: all lookups of a thread advance together, one probe each per round, without branches:
+  // pos = number of list entries below the token
+  int pos[kMaxSpt];
+#pragma unroll
+  for (int i = 0; i < kMaxSpt; ++i) pos[i] = 0;
+  int top = 1;
+  while (top < k) top <<= 1;
+  for (int step = top; step > 0; step >>= 1) {
+#pragma unroll
+    for (int i = 0; i < kMaxSpt; ++i) {
+      if (i < spt) {  // uniform: the probes are bound by the LDS, so none is spent on slots nobody has
+        const int nxt = pos[i] + step;
+        const int probe = l_new[min(nxt, k) - 1];
+        pos[i] = (nxt <= k && probe < mytok[i]) ? nxt : pos[i];
+      }
+    }
+  }
+  bool evict[kMaxSpt];
+  int ce = 0;
+#pragma unroll
+  for (int i = 0; i < kMaxSpt; ++i) {
+    evict[i] = false;
+    if (j0 + i < j1) {
+      const bool found = was_valid && pos[i] < k && l_new[pos[i]] == mytok[i];
+      if (found) l_hit[pos[i]] = 1;  // slots hold distinct tokens: one writer per entry
+      evict[i] = !found;
+      ce += !found;
+    }
+  }
+  int total;
+  int je = block_exclusive_scan<NT / 64>(ce, s_wave, &total);  // its barriers also publish l_hit
+  const int m = total;
+#pragma unroll
+  for (int i = 0; i < kMaxSpt; ++i)
+    if (evict[i]) {
+      l_ms[je] = j0 + i;
+      ms[je] = j0 + i;
+      ++je;
+    }
+  // 3
+  int cm = 0;
+#pragma unroll
+  for (int i = 0; i < kMaxSpt; ++i)
+    if (j0 + i < j1) cm += !l_hit[j0 + i];
+  int jm = block_exclusive_scan<NT / 64>(cm, s_wave, &total);
+#pragma unroll
+  for (int i = 0; i < kMaxSpt; ++i)
+    if (j0 + i < j1) {
+      const bool hit = l_hit[j0 + i] != 0;
+      hm[j0 + i] = (uint8_t)hit;
+      if (!hit) {
+        if (jm < k) {
+          l_mt[jm] = l_new[j0 + i];
+          mt[jm] = l_new[j0 + i];
+        }
+        ++jm;
+      }
+    }
+  __syncthreads();
+  // 4
+  for (int i = tid; i < m; i += NT) {
+    const int slot = l_ms[i], tok = l_mt[i];
+    sl[slot] = tok;
+    ft[slot] = tok;
+  }
+  if (tid == 0) {
+    miss_count[p] = m;
+    valid[p] = 1;
+    atomicAdd(&stats[3], (u64)(k - m));
+    atomicAdd(&stats[4], (u64)m);
+    if (src.slot[p % Hkv] >= 0) atomicAdd(&stats[5], (u64)m);
   }
 }
 
@@ -827,7 +1040,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
   if (reuse_flags[p]) return;
   __shared__ int s_wave[32];
   diff_phases<kDiffThreads, WPL>(bm_new + (size_t)p * words, bm_eq + (size_t)p * words, bm_old + (size_t)p * words,
-                            valid[p] != 0, sel_r[p], words, k, slot_idx + (size_t)p * k_max,
+                            valid[p] != 0, sel_r[(size_t)p * kSelStride], words, k, slot_idx + (size_t)p * k_max,
                             set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
                             miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max,
                             fetch_tok + (size_t)p * k_max, miss_count + p, valid + p, stats,

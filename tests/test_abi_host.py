@@ -50,7 +50,7 @@ def test_workspace_size_and_layout(lib):
     L = Q.qsac_workspace_layout(cfg)
     assert n == L.total and n > 64 * 32768 * 4
     assert L.n_pad == 32768 and L.words == 1024 and L.max_splits == 32
-    offs = [getattr(L, f) for f, _ in Q.qsac_ws_layout._fields_[:16]]
+    offs = [getattr(L, f) for f, _ in Q.qsac_ws_layout._fields_[:17]]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     cfg = Q.make_config(1, 8, 2, 5000, 100, Q.QSAC_F16)
     assert Q.qsac_workspace_layout(cfg).n_pad == 8192

@@ -210,7 +210,8 @@ def test_ties_across_many_waves_of_the_bitmap(H):
     K[:, :, 1::2] = K[0, 0, 1]
     K = K.to(torch.bfloat16)
     V = torch.randn((B, Hkv, N, 128), generator=g).to(torch.bfloat16)
-    for n_ctx, k in ((N, 30000), (40000, 15000)):
+    # (large-N diff on bitmaps, one-workgroup select, large-N diff on lists)
+    for n_ctx, k in ((N, 30000), (40000, 15000), (N, 5000)):
         sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, n_ctx, k, "bf16", K=K[:, :, :n_ctx].contiguous(),
                                             V=V[:, :, :n_ctx].contiguous())
         par = H.Parity(sess, "bf16", Kb, Ksb, Vsb)
@@ -224,6 +225,27 @@ def test_ties_across_many_waves_of_the_bitmap(H):
             assert (r.scores[0] == r.kth_score[0]).sum() > 1000
         assert par.n_band == 0
         sess.close()
+
+
+def test_ties_on_the_long_context_path(H):
+    """Above 262144 keys the set is emitted as a token list by the whole grid: thousands of keys equal the
+    k-th key, in every chunk, and only the first r of them (by index) may be taken."""
+    B, Hq, Hkv, N, k = 1, 4, 1, 270000, 6000
+    g = torch.Generator().manual_seed(6)
+    K = torch.randn((B, Hkv, N, 128), generator=g)
+    K[:, :, 1::2] = K[0, 0, 1]
+    K = K.to(torch.bfloat16)
+    V = torch.randn((B, Hkv, N, 128), generator=g).to(torch.bfloat16)
+    sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, N, k, "bf16", K=K, V=V)
+    par = H.Parity(sess, "bf16", Kb, Ksb, Vsb)
+    base = K[0, 0, 1].double().numpy()
+    rng = np.random.default_rng(4)
+    for t in range(3):
+        q = np.tile(base / np.linalg.norm(base), (B, Hq, 1)) + 0.02 * rng.standard_normal((B, Hq, 128))
+        r = par.step(q, 2.0, k, label=f"long-context ties step {t}")
+        assert (r.scores[0] == r.kth_score[0]).sum() > 1000
+    assert par.n_band == 0
+    sess.close()
 
 
 def exact_tie_case(H, flags):
