@@ -453,7 +453,7 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   };
   auto combine = [&]() {
     if (n_splits > 1)
-      qsac_combine_kernel<<<P * G, 128, 0, sm>>>(part_ml, part_acc, a->reuse_flags, a->out, Hq, Hkv, G, n_splits,
+      qsac_combine_kernel<<<P * G, n_splits > 16 ? 512 : 128, 0, sm>>>(part_ml, part_acc, a->reuse_flags, a->out, Hq, Hkv, G, n_splits,
                                                  L.max_splits, 0);
   };
   const bool side_attn = c->overlap && !c->fill_kernel;  // reused heads are attended to beside the select

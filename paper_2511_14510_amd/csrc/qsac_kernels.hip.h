@@ -1596,11 +1596,13 @@ __global__ __launch_bounds__(256) void qsac_attn_kernel(AttnArgs A, FillSrc src)
   attn_body<DT, G, FETCH, 4>(A, src, p, split, S);
 }
 
-// One workgroup of 128 threads per query head: merges the attention splits and normalises.
+// One workgroup per query head: merges the attention splits and normalises.  128 threads (one
+// per channel) times blockDim.x / 128 groups (1 or 4); group j takes the splits 8j .. 8j+7,
+// 8(j + groups) .. and the groups are merged through LDS.
 // (Merging inside the attention kernel, by the last workgroup of a pair to finish, needs a
 // device-scope release/acquire per workgroup, which on this multi-die part writes back and
 // invalidates L2 and cost ten times what this launch does.)
-__global__ __launch_bounds__(128) void qsac_combine_kernel(const float* __restrict__ part_ml,
+__global__ __launch_bounds__(512) void qsac_combine_kernel(const float* __restrict__ part_ml,
                                                            const float* __restrict__ part_acc,
                                                            const uint8_t* __restrict__ reuse_flags,
                                                            float* __restrict__ out, int Hq, int Hkv, int G,
@@ -1608,14 +1610,15 @@ __global__ __launch_bounds__(128) void qsac_combine_kernel(const float* __restri
   const int pg = blockIdx.x;  // p * G + g
   const int p = pg / G, g = pg % G;
   if (!pair_selected(which, reuse_flags, p)) return;
-  const int d = threadIdx.x;
+  __shared__ float s_m[4][kD], s_l[4][kD], s_a[4][kD];
+  const int d = threadIdx.x & 127, grp = threadIdx.x >> 7, groups = blockDim.x >> 7;
   const float kNegInf = -__builtin_inff();
   const float* ml = part_ml + (size_t)pg * max_splits * 2;
   const float* pa = part_acc + (size_t)pg * max_splits * kD;
   // eight splits at a time: their loads are all issued before the first is used, and the chunks
-  // are merged online in split order
+  // are merged online
   float M = kNegInf, L = 0.f, A = 0.f;
-  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+  for (int s0 = grp * 8; s0 < n_splits; s0 += groups * 8) {
     float mv[8], lv[8], av[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -1638,6 +1641,24 @@ __global__ __launch_bounds__(128) void qsac_combine_kernel(const float* __restri
       A += av[i] * wt;
     }
     M = Mc;
+  }
+  if (groups > 1) {  // uniform
+    s_m[grp][d] = M;
+    s_l[grp][d] = L;
+    s_a[grp][d] = A;
+    __syncthreads();
+    if (grp != 0) return;
+    float Mc = M;
+    for (int j = 1; j < groups; ++j) Mc = fmaxf(Mc, s_m[j][d]);
+    float Ls = 0.f, As = 0.f;
+    for (int j = 0; j < groups; ++j) {
+      const float mj = s_m[j][d];
+      const float wt = (mj == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mj - Mc);
+      Ls += s_l[j][d] * wt;
+      As += s_a[j][d] * wt;
+    }
+    L = Ls;
+    A = As;
   }
   const int b = p / Hkv, h = p % Hkv;
   out[((size_t)b * Hq + (size_t)h * G + g) * kD + d] = A / L;
