@@ -22,9 +22,9 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes the scoring kernel moves per missing pair, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (profiles/qsac_step_kernels__llama3_8b_32k_all_miss__pmc_{fetch,write}_size.txt): per launch of 64 missing
-# pairs FETCH_SIZE = 262423.7 units of 2.000 KiB and WRITE_SIZE = 8245.2 units of 1.000 KiB (units calibrated
+# pairs FETCH_SIZE = 262431.7 units of 2.000 KiB and WRITE_SIZE = 8242.8 units of 1.000 KiB (units calibrated
 # against the 256-MiB qsac_copy_kernel of the same runs).  bench.py cannot collect counters itself.
-PMC_SCORE_BYTES_PER_MISSING_PAIR = {"llama3_8b_32k": (262423.7 * 2.000 + 8245.2 * 1.000) * 1024 / 64}
+PMC_SCORE_BYTES_PER_MISSING_PAIR = {"llama3_8b_32k": (262431.7 * 2.000 + 8242.8 * 1.000) * 1024 / 64}
 
 
 def parse():

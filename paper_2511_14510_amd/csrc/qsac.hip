@@ -59,8 +59,9 @@ int attn_rows(int P, int k) {
 // Rank, within the select's sample of 4096 keys (one key in vpt), whose key bounds the candidates of the
 // guided select from below: the count C of keys at or above it has mean vpt * r and a standard deviation
 // below vpt * sqrt(r); r solves  vpt * (r - 6 sqrt(r)) = k, which puts k six deviations below the mean.
-// 0 (no guided select) when the candidates might not fit the list.
+// 0 (no guided select) when the candidates might not fit the list, or the context is short.
 int select_sample_rank(int k, int vpt) {
+  if (vpt < 8) return 0;  // up to 16384 keys the three full passes are as quick (measured)
   const double x = 3.0 + std::sqrt(9.0 + (double)k / vpt);
   const int r = (int)std::ceil(x * x);
   const double upper = (double)vpt * (r + 6.0 * std::sqrt((double)r));
