@@ -9,9 +9,12 @@
 //   select   radix select of the k-th largest key (11 + 11 + 10 bits), ties by lowest index,
 //            ascending index list, hit mask against the cached tokens, (slot, token) miss
 //            list, slot table update.  Up to kSmallMaxN keys: one workgroup per pair does all
-//            of it with its bitmaps in LDS.  Beyond: the first histogram is fused into the
-//            scoring kernel and the levels run as grid-wide kernels (refine1, refine2, mark,
-//            diff) so that a few pairs with very long contexts still fill the chip.
+//            of it with its bitmaps in LDS (above 16384 keys on a candidate list cut out by a
+//            sampled bound).  Beyond: the first histogram is fused into the scoring kernel and
+//            the levels run as grid-wide kernels (refine1, refine2, mark) so that a few pairs
+//            with very long contexts still fill the chip, followed by the one-workgroup diff
+//            on the bitmaps, or, above 262144 keys, by a grid-wide emit of the set as a token
+//            list and a one-workgroup diff on that list.
 //   fill     copies the missing K / V rows from the fill sources into the slots; by default this
 //            is folded into the attention kernel's row loads ("fill on read"), the separate
 //            kernel (optionally on a side stream) is kept as the alternative

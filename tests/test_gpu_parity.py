@@ -173,11 +173,13 @@ def test_attention_with_several_tiles_per_wave(H):
     run_chain(H, B=4, Hq=8, Hkv=2, N=40000, k=3000, k_max=3000, dtype="bf16", steps=5, tau=0.93, expect_both=False)
 
 
-@pytest.mark.parametrize("flags,N", [(0, 140001), (Q.QSAC_FLAG_SCORE_VALU, 140001), (0, 270001)])
-def test_large_n_path(H, flags, N):
-    """N above 65536 takes the grid-wide select (histogram fused into scoring, refine, mark, diff); above
-    262144 keys the diff holds 32 bitmap words per lane instead of 8."""
-    run_chain(H, B=1, Hq=8, Hkv=2, N=N, k=700, k_max=700, dtype="bf16", steps=6, flags=flags, tau=0.93)
+@pytest.mark.parametrize("flags,N,k", [(0, 140001, 700), (Q.QSAC_FLAG_SCORE_VALU, 140001, 700), (0, 270001, 700),
+                                         (0, 270001, 8200), (Q.QSAC_FLAG_FILL_KERNEL, 270001, 333)])
+def test_large_n_path(H, flags, N, k):
+    """N above 65536 takes the grid-wide select (histogram fused into scoring, refine, mark, diff on bitmaps);
+    above 262144 keys the set is emitted as a token list by the whole grid and diffed from LDS, unless k is
+    above 8192: then the bitmap diff runs with 32 words per lane instead of 8."""
+    run_chain(H, B=1, Hq=8, Hkv=2, N=N, k=k, k_max=k, dtype="bf16", steps=6, flags=flags, tau=0.93)
 
 
 def test_adaptive_thresholds_drive_the_gate(H):
