@@ -44,6 +44,9 @@ def parse():
                     help="give the library a second stream (attention of reused heads, or the fill kernel, runs on it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the stage-timing passes")
+    ap.add_argument("--calibration-reads", type=int, default=0,
+                    help="after the run, launch this many read-only kernels (qsac_calibration_read) of the attention "
+                         "launch's and of the all-miss scoring launch's size: what a launch of that size can reach")
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="launch this many plain 256 MiB copies first (qsac_copy_kernel), to scale profiler counters")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = sized to ~15 s)")
@@ -248,6 +251,27 @@ def main():
                 result[tag] = {"bound": "pcie", "kernel": "qsac_fill_kernel", "bytes_per_launch": by,
                                "us_per_launch": uf[3], "achieved": gbs, "peak": peak, "unit": "GB/s",
                                "frac": gbs / peak, "peak_kind": "measured hipMemcpyAsync pinned H2D, 1 GiB"}
+
+    # ---- read-only launches of the sizes of the two HBM-bound kernels (a yardstick, not part of the step)
+    if a.calibration_reads:
+        pool = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        result["read_only_launch"] = {}
+        for name, nbytes in (("attn", 512 * w.k * w.P), ("score_all_miss", 256 * w.N * w.P)):
+            nbytes = min(nbytes, 512 << 20) // 16 * 16
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            us = []
+            for r in range(a.calibration_reads + 2):
+                off = (r * nbytes) % ((1 << 30) - nbytes + 256) // 256 * 256     # rotate: nothing stays in a cache
+                ev[0].record()
+                Q.qsac_calibration_read(pool.data_ptr() + off, nbytes, sink.data_ptr())   # on the null stream, as the events
+                ev[1].record()
+                ev[1].synchronize()
+                if r >= 2:
+                    us.append(1e3 * ev[0].elapsed_time(ev[1]))
+            result["read_only_launch"][name] = {"bytes": nbytes, "us_by_events": sum(us) / len(us),
+                                                "GBps_by_events": nbytes / (sum(us) / len(us) * 1e-6) / 1e9}
+        del pool
 
     # ---- the oracle on the host cores of this machine, a bounded sample of the same workload
     if not a.no_cpu_baseline:

@@ -241,6 +241,15 @@ int qsac_reuse_difficulty(const float *tau, const float *avg_sim, int32_t n, flo
  */
 int qsac_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/*
+ * Measurement aid: enqueues a kernel that only reads `bytes` bytes (a multiple of 16) at DEVICE pointer
+ * `src` (16-byte aligned) on `stream`: 2048 workgroups, a contiguous span each, eight 16-byte loads per
+ * thread in flight.  Its duration is what a launch of that size can reach on the part with no arithmetic,
+ * the yardstick for the scoring and attention kernels (Section 5.1 of the paper prices them in bytes).
+ * `sink` is a DEVICE u32 that is (practically never) written; it keeps the loads alive.
+ */
+int qsac_calibration_read(const void *src, size_t bytes, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ QSAC_MAX_GROUP, QSAC_MAX_KV_HEADS, QSAC_HEAD_DIM = 8, 64, 128
 
 EXPORTS = ("qsac_workspace_bytes", "qsac_workspace_layout", "qsac_init", "qsac_reset", "qsac_step",
            "qsac_get_stats", "qsac_free", "qsac_strerror", "qsac_last_hip_error", "qsac_num_stages",
-           "qsac_stage_name", "qsac_get_stage_ms", "qsac_calibration_copy", "qsac_adaptive_thresholds",
+           "qsac_stage_name", "qsac_get_stage_ms", "qsac_calibration_copy", "qsac_calibration_read", "qsac_adaptive_thresholds",
            "qsac_reuse_difficulty")
 
 
@@ -82,6 +82,7 @@ def load():
         L.qsac_stage_name.argtypes = [C.c_int]
         L.qsac_get_stage_ms.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
         L.qsac_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.qsac_calibration_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         fp = C.POINTER(C.c_float)
         L.qsac_adaptive_thresholds.argtypes = [fp, C.c_int32, C.c_float, C.c_float, fp]
         L.qsac_reuse_difficulty.argtypes = [fp, fp, C.c_int32, C.c_float, fp]
@@ -156,6 +157,12 @@ def qsac_calibration_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int =
     rc = load().qsac_calibration_copy(dst_ptr, src_ptr, nbytes, stream)
     if rc:
         raise QsacError(rc, "qsac_calibration_copy")
+
+
+def qsac_calibration_read(src_ptr: int, nbytes: int, sink_ptr: int, stream: int = 0) -> None:
+    rc = load().qsac_calibration_read(src_ptr, nbytes, sink_ptr, stream)
+    if rc:
+        raise QsacError(rc, "qsac_calibration_read")
 
 
 def _floats(xs):

@@ -655,6 +655,16 @@ int qsac_calibration_copy(void* dst, const void* src, size_t bytes, void* stream
   return QSAC_OK;
 }
 
+int qsac_calibration_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink) return QSAC_ENULL;
+  if (!aligned16(src) || (bytes & 15u) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return QSAC_EALIGN;
+  if (bytes == 0) return QSAC_OK;
+  qsac_read_kernel<<<2048, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const v4u*>(src), bytes / 16,
+                                                                      static_cast<u32*>(sink));
+  HIP_TRY(hipGetLastError());
+  return QSAC_OK;
+}
+
 int qsac_num_stages(void) { return kStages; }
 
 const char* qsac_stage_name(int i) { return (i >= 0 && i < kStages) ? kStageNames[i] : nullptr; }
