@@ -207,3 +207,12 @@ def test_sink_recent_and_append_validation(lib):
     for kw in (dict(n_sink=-1), dict(n_sink=200, n_recent=100), dict(append_capacity=-5)):
         bad = Q.make_config(1, 8, 2, 4096, 256, Q.QSAC_F16, Q.QSAC_FLAG_DRY_RUN, **kw)
         assert Q.qsac_workspace_bytes(bad) == 0
+
+
+def test_calibration_entry_points_validate_before_touching_a_device(lib):
+    # NULL and misaligned arguments are turned down on the host; nothing is launched
+    assert lib.qsac_calibration_copy(None, None, 256, None) == Q.QSAC_ENULL
+    assert lib.qsac_calibration_read(None, 256, None, None) == Q.QSAC_ENULL
+    assert lib.qsac_calibration_copy(4096, 8192, 24, None) == Q.QSAC_EALIGN      # size not a multiple of 16
+    assert lib.qsac_calibration_read(4096 + 8, 256, 4096, None) == Q.QSAC_EALIGN  # source not 16-byte aligned
+    assert lib.qsac_calibration_read(4096, 0, 4096, None) == Q.QSAC_OK           # nothing to read: no launch

@@ -358,3 +358,15 @@ def test_guided_select(H, N, k, k_max):
     """The one-workgroup select takes its top-k from the keys above a sampled bound when it can, and from all
     keys when it cannot (k = N, k too large for the candidate list): sets, masks and slots against the oracle."""
     par = run_chain(H, B=3, Hq=8, Hkv=2, N=N, k=k, k_max=k_max, dtype="bf16", steps=12, seed=77, side_stream=False)
+
+
+def test_calibration_kernels_run(H):
+    """The two measurement aids: the copy moves the bytes, the read-only kernel leaves its sink alone."""
+    src = torch.arange(1 << 18, dtype=torch.int32, device="cuda:0")
+    dst = torch.zeros_like(src)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    Q.qsac_calibration_copy(dst.data_ptr(), src.data_ptr(), src.numel() * 4)
+    Q.qsac_calibration_read(src.data_ptr(), src.numel() * 4, sink.data_ptr())
+    Q.qsac_calibration_read(src.data_ptr() + 16, 4096 + 16, sink.data_ptr())      # a ragged span
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src) and int(sink.item()) == 0
