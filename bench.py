@@ -44,6 +44,9 @@ def parse():
                     help="give the library a second stream (attention of reused heads, or the fill kernel, runs on it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the stage-timing passes")
+    ap.add_argument("--k-fill-from-hbm", action="store_true",
+                    help="not the workload as specified: take the missing K rows from the HBM copy of K that scoring "
+                         "reads (K_src = K_dev), so that only V rows cross PCIe")
     ap.add_argument("--calibration-reads", type=int, default=0,
                     help="after the run, launch this many read-only kernels (qsac_calibration_read) of the attention "
                          "launch's and of the all-miss scoring launch's size: what a launch of that size can reach")
@@ -95,6 +98,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
     Q.load()
     w = W.CONFIGS[a.workload]
+    if a.k_fill_from_hbm:
+        import dataclasses
+        w = dataclasses.replace(w, host_k=False)
     tau = w.tau if a.tau is None else a.tau
     K_steps, W_steps = a.steps, a.warmup
     total = K_steps + W_steps
