@@ -370,3 +370,37 @@ def test_calibration_kernels_run(H):
     Q.qsac_calibration_read(src.data_ptr() + 16, 4096 + 16, sink.data_ptr())      # a ragged span
     torch.cuda.synchronize()
     assert torch.equal(dst, src) and int(sink.item()) == 0
+
+
+def test_guided_select_falls_back_when_its_sample_misleads(H):
+    """1000 keys with outstanding scores sit exactly where the one-workgroup select samples (N = 32768: the
+    first key of key vectors 0..1023, 2048..3071, ...), so the sampled bound lands among them, fewer than k keys
+    pass it, and the full radix path has to take over: same sets as the oracle, and the counters say so."""
+    B, Hq, Hkv, N, k = 1, 4, 1, 32768, 2048
+    g = torch.Generator().manual_seed(12)
+    K = torch.randn((B, Hkv, N, 128), generator=g)
+    d = torch.randn(128, generator=g)
+    d = d / d.norm()
+    sampled = np.concatenate([4 * np.arange(2048 * j, 2048 * j + 1024) for j in range(4)])
+    special = sampled[np.random.default_rng(1).choice(sampled.size, 1000, replace=False)]
+    K[0, 0, special] = 40.0 * d + 0.05 * torch.randn((1000, 128), generator=g)
+    K = K.to(torch.bfloat16)
+    V = torch.randn((B, Hkv, N, 128), generator=g).to(torch.bfloat16)
+    sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, N, k, "bf16", K=K, V=V, side_stream=False)
+    par = H.Parity(sess, "bf16", Kb, Ksb, Vsb)
+    rng = np.random.default_rng(2)
+    for t in range(4):
+        q = np.tile(d.double().numpy(), (B, Hq, 1)) + 0.05 * rng.standard_normal((B, Hq, 128))
+        par.step(q, 2.0, k, label=f"misleading sample step {t}")
+    st = sess.stats()
+    assert st["miss_heads"] == 4 and st["guided_selects"] == 0
+    sess.close()
+    # the same shape with ordinary keys takes the guided path
+    sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, N, k, "bf16", seed=12, side_stream=False)
+    par = H.Parity(sess, "bf16", Kb, Ksb, Vsb)
+    chain = W.QueryChain(B, Hq, 128, 0.95, 12)
+    for t in range(4):
+        par.step(chain.next(), 2.0, k, label=f"ordinary keys step {t}")
+    st = sess.stats()
+    assert st["miss_heads"] == 4 and st["guided_selects"] == 4
+    sess.close()
