@@ -436,11 +436,13 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   if (c->cfg.dtype == QSAC_F16)
     qsac_gate_kernel<0><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
-                                           a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max);
+                                           a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max,
+                                           !c->small);
   else
     qsac_gate_kernel<1><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
-                                           a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max);
+                                           a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max,
+                                           !c->small);
   const int rows = attn_rows(P, k + a->n_app);
   const int n_splits = (k + a->n_app + rows - 1) / rows;
   dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
@@ -519,8 +521,8 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
       qsac_emit_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, bm_new, bm_eq, chunk_cnt, sel_r, set_sorted,
                                                 a->topk_idx, L.words, k, k_max);
       qsac_diff_list_kernel<<<P, kDiffThreads, (size_t)k * 13, sm>>>(a->reuse_flags, valid, a->slot_idx, set_sorted,
-                                                                    a->hit_mask, miss_count, miss_slot, miss_tok,
-                                                                    fetch_tok, stats, src, Hkv, k, k_max);
+                                                                    a->topk_idx, a->hit_mask, miss_count, miss_slot,
+                                                                    miss_tok, fetch_tok, stats, src, Hkv, k, k_max);
     } else {
       qsac_mark_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, bm_new, bm_eq, bm_old, sel_r, nullptr, N,
                                                 L.n_pad, L.words, k);

@@ -299,7 +299,7 @@ __global__ __launch_bounds__(256) void qsac_gate_kernel(
     TauArg tau, const u32* __restrict__ valid, const int* __restrict__ set_sorted, int* __restrict__ topk_idx,
     uint8_t* __restrict__ hit_mask, uint8_t* __restrict__ reuse_flags, float* __restrict__ sim_out,
     int* __restrict__ miss_count, u32* __restrict__ hist, u64* __restrict__ stats, int Hq, int Hkv, int G,
-    int k, int k_max) {
+    int k, int k_max, bool clear_hist) {
   const int p = blockIdx.x;
   const int b = p / Hkv, h = p % Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -346,18 +346,28 @@ __global__ __launch_bounds__(256) void qsac_gate_kernel(
   }
   __syncthreads();
   if (s_reuse) {
-    // cache hit: report the cached set as it stands
-    const int* src = set_sorted + (size_t)p * k_max;
-    for (int j = threadIdx.x; j < k; j += 256) {
-      topk_idx[(size_t)p * k + j] = src[j];
-      hit_mask[(size_t)p * k + j] = 1;
-    }
+    // cache hit: the cached set is reported as it stands by report_cached_set, in the select's launch,
+    // where it costs nothing (the pairs that missed keep that launch busy far longer)
     if (threadIdx.x == 0) miss_count[p] = 0;
   } else {
     // cache miss: relabel now (the rows follow in the fill), and clear this pair's histograms
+    // (only the grid-wide select uses them)
     for (int i = threadIdx.x; i < G * 64; i += 256) pq32[i] = q32[i];
-    u32* hp = hist + (size_t)p * 3 * kBins;
-    for (int i = threadIdx.x; i < 3 * kBins; i += 256) hp[i] = 0;
+    if (clear_hist) {
+      u32* hp = hist + (size_t)p * 3 * kBins;
+      for (int i = threadIdx.x; i < 3 * kBins; i += 256) hp[i] = 0;
+    }
+  }
+}
+
+// Cache hit: topk_idx <- the cached set (ascending), hit_mask <- 1.  Called by the workgroup that
+// would have selected for the pair had it missed.
+__device__ __forceinline__ void report_cached_set(const int* __restrict__ set_sorted, int* __restrict__ topk_idx,
+                                                  uint8_t* __restrict__ hit_mask, int p, int k, int k_max) {
+  const int* src = set_sorted + (size_t)p * k_max;
+  for (int j = threadIdx.x; j < k; j += blockDim.x) {
+    topk_idx[(size_t)p * k + j] = src[j];
+    hit_mask[(size_t)p * k + j] = 1;
   }
 }
 
@@ -730,11 +740,14 @@ __global__ __launch_bounds__(256) void qsac_emit_kernel(const uint8_t* __restric
 constexpr int kDiffListMax = 8192;
 __global__ __launch_bounds__(kDiffThreads) void qsac_diff_list_kernel(
     const uint8_t* __restrict__ reuse_flags, u32* __restrict__ valid, int* __restrict__ slot_idx,
-    const int* __restrict__ set_sorted, uint8_t* __restrict__ hit_mask, int* __restrict__ miss_count,
-    int* __restrict__ miss_slot, int* __restrict__ miss_tok, int* __restrict__ fetch_tok, u64* __restrict__ stats,
-    FillSrc src, int Hkv, int k, int k_max) {
+    const int* __restrict__ set_sorted, int* __restrict__ topk_idx, uint8_t* __restrict__ hit_mask,
+    int* __restrict__ miss_count, int* __restrict__ miss_slot, int* __restrict__ miss_tok,
+    int* __restrict__ fetch_tok, u64* __restrict__ stats, FillSrc src, int Hkv, int k, int k_max) {
   const int p = blockIdx.x;
-  if (reuse_flags[p]) return;
+  if (reuse_flags[p]) {
+    report_cached_set(set_sorted, topk_idx, hit_mask, p, k, k_max);
+    return;
+  }
   constexpr int NT = kDiffThreads;
   constexpr int kMaxSpt = kDiffListMax / NT;
   extern __shared__ int s_lists[];
@@ -1040,7 +1053,10 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
     int* __restrict__ miss_tok, int* __restrict__ fetch_tok, u64* __restrict__ stats, FillSrc src, int Hkv,
     int words, int k, int k_max) {
   const int p = blockIdx.x;
-  if (reuse_flags[p]) return;
+  if (reuse_flags[p]) {
+    report_cached_set(set_sorted, topk_idx, hit_mask, p, k, k_max);
+    return;
+  }
   __shared__ int s_wave[32];
   diff_phases<kDiffThreads, WPL>(bm_new + (size_t)p * words, bm_eq + (size_t)p * words, bm_old + (size_t)p * words,
                             valid[p] != 0, sel_r[(size_t)p * kSelStride], words, k, slot_idx + (size_t)p * k_max,
@@ -1245,7 +1261,10 @@ template <int VPT, int NT>
 __global__ __launch_bounds__(NT) void qsac_select_small_kernel(SelArgs A, FillSrc src) {
   extern __shared__ u32 s_dyn[];
   const int p = blockIdx.x;
-  if (A.reuse_flags[p]) return;
+  if (A.reuse_flags[p]) {
+    report_cached_set(A.set_sorted, A.topk_idx, A.hit_mask, p, A.k, A.k_max);
+    return;
+  }
   select_small_body<VPT, NT>(A, src, p, s_dyn);
 }
 
