@@ -1447,8 +1447,10 @@ __device__ __forceinline__ void attn_body(const AttnArgs& A, const FillSrc& src,
       int row = t0 + 4 * j + quarter;
       row = row < s_end ? row : s_end - 1;
       const v4u* from = row < k ? slots + (size_t)row * kRowU4 : app + (size_t)(row - k) * kRowU4;
-      if (FETCH && tok[j] >= 0) from = src + (size_t)tok[j] * kRowU4;
-      dst[j] = from[m];
+      if (FETCH && tok[j] >= 0)
+        dst[j] = src[(size_t)tok[j] * kRowU4 + m];
+      else
+        dst[j] = __builtin_nontemporal_load(from + m);
     }
   };
   // fetched rows go into their slots
