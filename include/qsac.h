@@ -29,7 +29,11 @@
  *
  * Error behaviour: every function returns 0 (QSAC_OK) or a negative code; no
  * exceptions, no aborts.  Arguments are validated on the host before anything
- * is enqueued, so a failed call has no effect on the device.
+ * is enqueued, so a call that fails validation (every code but QSAC_EHIP) has no
+ * effect on the device or on the context.  QSAC_EHIP from qsac_step() means a HIP
+ * call failed after part of the step may have been enqueued: the context then
+ * refuses further steps with QSAC_ESTATE until qsac_reset() has invalidated the
+ * caches, and its step counter does not count the failed step.
  */
 #ifndef QSAC_H
 #define QSAC_H
@@ -47,10 +51,10 @@ enum {
   QSAC_OK = 0,
   QSAC_EINVAL = -1,     /* a field has an unsupported value                     */
   QSAC_ENULL = -2,      /* a required pointer is NULL                           */
-  QSAC_ERANGE = -3,     /* k, k_max, n_ctx or a head count is out of range      */
+  QSAC_ERANGE = -3,     /* k, k_max, n_ctx (at most 2^20) or a head count is out of range */
   QSAC_EWORKSPACE = -4, /* workspace missing, misaligned or too small           */
   QSAC_EHIP = -5,       /* a HIP runtime call failed (see qsac_last_hip_error)  */
-  QSAC_ESTATE = -6,     /* bad handle, or k changed without qsac_reset          */
+  QSAC_ESTATE = -6,     /* bad handle, k changed without qsac_reset, or a step failed with QSAC_EHIP */
   QSAC_EALIGN = -7      /* a tensor pointer is not 16-byte aligned              */
 };
 
@@ -121,6 +125,17 @@ typedef struct {
 } qsac_ws_layout;
 
 /*
+ * Per-step scalars kept in DEVICE memory, for a step that is captured once into a graph and replayed
+ * (qsac_graph_capture): a replay cannot take new host values, so the kernels read these at run time and the
+ * caller rewrites the block between replays (ordered on stream_main, e.g. by a small asynchronous copy).
+ */
+typedef struct {
+  float tau[QSAC_MAX_KV_HEADS]; /* thresholds tau_i, one per KV head (entries past n_kv_heads are ignored)   */
+  int32_t n_app;                /* valid rows of the append-only buffer; clamped to [0, qsac_step_args.n_app] */
+  int32_t reserved[3];
+} qsac_dev_params;
+
+/*
  * Arguments of one step.  Everything is caller-owned and stays valid until
  * stream_main has run past the step.
  */
@@ -154,6 +169,10 @@ typedef struct {
   const void *K_app;         /* DEVICE e [B,Hkv,append_capacity,D]                                        */
   const void *V_app;         /* DEVICE e [B,Hkv,append_capacity,D]                                        */
   int32_t n_app;             /* valid rows, 0 <= n_app <= append_capacity                                 */
+  /* NULL, or per-step scalars in device memory.  Given one, the kernels take tau_i and the number of valid
+     append-buffer rows from it when they run (tau / n_tau above are then ignored and may be NULL), and n_app
+     above is the largest value the block will ever hold: it sizes the launch. */
+  const qsac_dev_params *dev_params; /* DEVICE, 16-byte aligned */
 } qsac_step_args;
 
 /* Cumulative since init / reset, summed over pairs. */
@@ -162,8 +181,10 @@ typedef struct {
   uint64_t reuse_heads;  /* pairs that took the reuse branch            */
   uint64_t miss_heads;   /* pairs that took the miss branch             */
   uint64_t slot_hits;    /* rows of a fresh top-k that were cached      */
-  uint64_t slot_misses;  /* rows filled from the fill sources           */
-  uint64_t resident_rows;/* of those, rows of resident heads (from HBM) */
+  uint64_t slot_misses;  /* rows filled from the fill sources (one row = a K row and a V row)     */
+  uint64_t bytes_filled_host; /* bytes of those rows that came from host memory (over PCIe)        */
+  uint64_t bytes_filled_dev;  /* bytes of those rows that came from HBM; host + dev = 512 * slot_misses */
+  uint64_t resident_rows;/* of slot_misses, rows of resident heads (always from HBM)              */
   uint64_t guided_selects;/* misses whose top-k was taken from the candidates above a sampled bound */
   uint64_t reserved[1];
 } qsac_stats;
@@ -200,6 +221,23 @@ int qsac_free(qsac_ctx *ctx);
 
 const char *qsac_strerror(int code);
 
+/*
+ * One step as a replayable graph.  The paper runs the decode step from a captured graph because kernel
+ * launches otherwise dominate short steps (Section 2.3), which is possible only while the step's launch
+ * topology is static and no host decision sits inside it (Section 5.2, last paragraph): both hold here, the
+ * gate's outcome is consumed on the device.  qsac_graph_capture() records the launches of one qsac_step(ctx,
+ * args) on stream_main into a graph without running them; args->dev_params is required, since tau and the
+ * append-buffer row count of a replay come from device memory.  Every pointer in args (q included: the caller
+ * copies each new query into that buffer) and args->k are bound into the graph.  qsac_graph_launch() enqueues
+ * one replay on stream_main and counts as one step; replays and plain qsac_step() calls on the same ctx may be
+ * mixed.  Not available for contexts created with QSAC_FLAG_PROFILE or QSAC_FLAG_DRY_RUN (QSAC_ESTATE).
+ * qsac_graph_free() releases the graph; the ctx must outlive it.
+ */
+typedef struct qsac_graph qsac_graph;
+int qsac_graph_capture(qsac_ctx *ctx, const qsac_step_args *args, qsac_graph **out);
+int qsac_graph_launch(qsac_graph *graph);
+int qsac_graph_free(qsac_graph *graph);
+
 /* hipError_t of the last failing HIP call on this thread (0 if none). */
 int qsac_last_hip_error(void);
 
@@ -233,22 +271,6 @@ int qsac_adaptive_thresholds(const float *importance, int32_t n, float eta, floa
  * heads with the largest D_i are the candidates for resident caching.
  */
 int qsac_reuse_difficulty(const float *tau, const float *avg_sim, int32_t n, float eps, float *d_out);
-
-/*
- * Measurement aid: enqueues a plain device-to-device copy (qsac_copy_kernel) of `bytes` bytes
- * (a multiple of 16, both pointers DEVICE and 16-byte aligned) on `stream`.  It reads `bytes` and
- * writes `bytes`, which is what profiler memory counters are scaled against.
- */
-int qsac_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
-
-/*
- * Measurement aid: enqueues a kernel that only reads `bytes` bytes (a multiple of 16) at DEVICE pointer
- * `src` (16-byte aligned) on `stream`: 2048 workgroups, a contiguous span each, eight 16-byte loads per
- * thread in flight.  Its duration is what a launch of that size can reach on the part with no arithmetic,
- * the yardstick for the scoring and attention kernels (Section 5.1 of the paper prices them in bytes).
- * `sink` is a DEVICE u32 that is (practically never) written; it keeps the loads alive.
- */
-int qsac_calibration_read(const void *src, size_t bytes, void *sink, void *stream);
 
 #ifdef __cplusplus
 }

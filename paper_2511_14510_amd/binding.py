@@ -13,6 +13,7 @@ import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "csrc", "libqsac.so")
+CALIB_LIB_PATH = os.path.join(HERE, "csrc", "libqsac_calib.so")
 
 QSAC_F16, QSAC_BF16 = 0, 1
 QSAC_OK, QSAC_EINVAL, QSAC_ENULL, QSAC_ERANGE = 0, -1, -2, -3
@@ -22,8 +23,9 @@ QSAC_MAX_GROUP, QSAC_MAX_KV_HEADS, QSAC_HEAD_DIM = 8, 64, 128
 
 EXPORTS = ("qsac_workspace_bytes", "qsac_workspace_layout", "qsac_init", "qsac_reset", "qsac_step",
            "qsac_get_stats", "qsac_free", "qsac_strerror", "qsac_last_hip_error", "qsac_num_stages",
-           "qsac_stage_name", "qsac_get_stage_ms", "qsac_calibration_copy", "qsac_calibration_read", "qsac_adaptive_thresholds",
-           "qsac_reuse_difficulty")
+           "qsac_stage_name", "qsac_get_stage_ms", "qsac_adaptive_thresholds", "qsac_reuse_difficulty",
+           "qsac_graph_capture", "qsac_graph_launch", "qsac_graph_free")
+CALIB_EXPORTS = ("qsac_calibration_copy", "qsac_calibration_read")
 
 
 class qsac_config(C.Structure):
@@ -47,16 +49,22 @@ class qsac_step_args(C.Structure):
                 ("tau", C.POINTER(C.c_float)), ("n_tau", C.c_int32), ("k", C.c_int32), ("out", C.c_void_p),
                 ("topk_idx", C.c_void_p), ("hit_mask", C.c_void_p), ("reuse_flags", C.c_void_p), ("sim", C.c_void_p),
                 ("V_res", C.c_void_p), ("res_slot", C.POINTER(C.c_int8)), ("n_res", C.c_int32),
-                ("K_app", C.c_void_p), ("V_app", C.c_void_p), ("n_app", C.c_int32)]
+                ("K_app", C.c_void_p), ("V_app", C.c_void_p), ("n_app", C.c_int32), ("dev_params", C.c_void_p)]
+
+
+class qsac_dev_params(C.Structure):
+    _fields_ = [("tau", C.c_float * QSAC_MAX_KV_HEADS), ("n_app", C.c_int32), ("reserved", C.c_int32 * 3)]
 
 
 class qsac_stats(C.Structure):
     _fields_ = [("steps", C.c_uint64), ("reuse_heads", C.c_uint64), ("miss_heads", C.c_uint64),
-                ("slot_hits", C.c_uint64), ("slot_misses", C.c_uint64), ("resident_rows", C.c_uint64),
-                ("guided_selects", C.c_uint64), ("reserved", C.c_uint64 * 1)]
+                ("slot_hits", C.c_uint64), ("slot_misses", C.c_uint64), ("bytes_filled_host", C.c_uint64),
+                ("bytes_filled_dev", C.c_uint64), ("resident_rows", C.c_uint64), ("guided_selects", C.c_uint64),
+                ("reserved", C.c_uint64 * 1)]
 
 
 _lib = None
+_calib = None
 
 
 def load():
@@ -81,13 +89,27 @@ def load():
         L.qsac_stage_name.restype = C.c_char_p
         L.qsac_stage_name.argtypes = [C.c_int]
         L.qsac_get_stage_ms.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
-        L.qsac_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
-        L.qsac_calibration_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.qsac_graph_capture.argtypes = [C.c_void_p, C.POINTER(qsac_step_args), C.POINTER(C.c_void_p)]
+        L.qsac_graph_launch.argtypes = [C.c_void_p]
+        L.qsac_graph_free.argtypes = [C.c_void_p]
         fp = C.POINTER(C.c_float)
         L.qsac_adaptive_thresholds.argtypes = [fp, C.c_int32, C.c_float, C.c_float, fp]
         L.qsac_reuse_difficulty.argtypes = [fp, fp, C.c_int32, C.c_float, fp]
         _lib = L
     return _lib
+
+
+def load_calib():
+    """Loads the measurement-aid library (the copy and read-only kernels the benchmark is held against)."""
+    global _calib
+    if _calib is None:
+        if not os.path.exists(CALIB_LIB_PATH):
+            raise RuntimeError(f"{CALIB_LIB_PATH} is not built; run `python -m paper_2511_14510_amd.build`")
+        L = C.CDLL(CALIB_LIB_PATH)
+        L.qsac_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.qsac_calibration_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        _calib = L
+    return _calib
 
 
 class QsacError(RuntimeError):
@@ -138,7 +160,8 @@ def qsac_get_stats(ctx) -> dict:
     if rc:
         raise QsacError(rc, "qsac_get_stats")
     return {n: int(getattr(st, n)) for n in ("steps", "reuse_heads", "miss_heads", "slot_hits", "slot_misses",
-                                             "resident_rows", "guided_selects")}
+                                             "bytes_filled_host", "bytes_filled_dev", "resident_rows",
+                                             "guided_selects")}
 
 
 def qsac_get_stage_ms(ctx):
@@ -154,15 +177,35 @@ def qsac_get_stage_ms(ctx):
 
 
 def qsac_calibration_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
-    rc = load().qsac_calibration_copy(dst_ptr, src_ptr, nbytes, stream)
+    rc = load_calib().qsac_calibration_copy(dst_ptr, src_ptr, nbytes, stream)
     if rc:
         raise QsacError(rc, "qsac_calibration_copy")
 
 
 def qsac_calibration_read(src_ptr: int, nbytes: int, sink_ptr: int, stream: int = 0) -> None:
-    rc = load().qsac_calibration_read(src_ptr, nbytes, sink_ptr, stream)
+    rc = load_calib().qsac_calibration_read(src_ptr, nbytes, sink_ptr, stream)
     if rc:
         raise QsacError(rc, "qsac_calibration_read")
+
+
+def qsac_graph_capture(ctx, args: qsac_step_args) -> C.c_void_p:
+    g = C.c_void_p()
+    rc = load().qsac_graph_capture(ctx, C.byref(args), C.byref(g))
+    if rc:
+        raise QsacError(rc, "qsac_graph_capture")
+    return g
+
+
+def qsac_graph_launch(graph) -> None:
+    rc = load().qsac_graph_launch(graph)
+    if rc:
+        raise QsacError(rc, "qsac_graph_launch")
+
+
+def qsac_graph_free(graph) -> None:
+    rc = load().qsac_graph_free(graph)
+    if rc:
+        raise QsacError(rc, "qsac_graph_free")
 
 
 def _floats(xs):
@@ -274,23 +317,53 @@ class Session:
 
     def step(self, q, tau, k):
         """Enqueues one step on the session's main stream; q is a device tensor [B,Hq,128]."""
+        qsac_step(self.ctx, self.step_args(q, tau, k))
+
+    def step_args(self, q, tau, k, dev_params=None, n_app_bound=None):
+        """The qsac_step_args of a step over this session's tensors.  With ``dev_params`` (a device tensor
+        holding a qsac_dev_params) tau is ignored and n_app is the bound ``n_app_bound``."""
         self._outputs_for(k)
-        taus = [float(tau)] if not hasattr(tau, "__len__") else [float(x) for x in tau]
-        tau_arr = (C.c_float * len(taus))(*taus)
         a = qsac_step_args()
+        if dev_params is None:
+            taus = [float(tau)] if not hasattr(tau, "__len__") else [float(x) for x in tau]
+            tau_arr = (C.c_float * len(taus))(*taus)
+            a._keep_tau = tau_arr
+            a.tau, a.n_tau = C.cast(tau_arr, C.POINTER(C.c_float)), len(taus)
+        else:
+            a.dev_params = dev_params.data_ptr()
         a.q, a.K_dev, a.K_src, a.V_src = q.data_ptr(), self.K_dev.data_ptr(), self.K_src.data_ptr(), self.V_src.data_ptr()
         a.K_slots, a.V_slots, a.slot_idx = self.K_slots.data_ptr(), self.V_slots.data_ptr(), self.slot_idx.data_ptr()
-        a.prev_q, a.tau, a.n_tau, a.k = self.prev_q.data_ptr(), C.cast(tau_arr, C.POINTER(C.c_float)), len(taus), k
+        a.prev_q, a.k = self.prev_q.data_ptr(), k
         a.out, a.topk_idx, a.hit_mask = self.out.data_ptr(), self.topk_idx.data_ptr(), self.hit_mask.data_ptr()
         a.reuse_flags, a.sim = self.reuse_flags.data_ptr(), self.sim.data_ptr()
-        if self.n_app:
-            a.K_app, a.V_app, a.n_app = self.K_app.data_ptr(), self.V_app.data_ptr(), self.n_app
+        n_app = self.n_app if n_app_bound is None else n_app_bound
+        if n_app:
+            a.K_app, a.V_app, a.n_app = self.K_app.data_ptr(), self.V_app.data_ptr(), n_app
         if self.V_res is not None:
             rs = (C.c_int8 * self.Hkv)(*self.res_slot)
             a._keep_rs = rs
             a.V_res, a.res_slot, a.n_res = self.V_res.data_ptr(), C.cast(rs, C.POINTER(C.c_int8)), self.V_res.shape[1]
         self._last_q = q  # keep the tensor alive until the stream has consumed it
-        qsac_step(self.ctx, a)
+        return a
+
+    def dev_params_table(self, taus, n_apps):
+        """Device tensor [T, sizeof(qsac_dev_params)] (uint8) holding one qsac_dev_params per step: row t has the
+        thresholds taus[t] (a scalar or one per KV head) and the append-buffer row count n_apps[t]."""
+        t = self.torch
+        size = C.sizeof(qsac_dev_params)
+        host = t.zeros((len(taus), size), dtype=t.uint8)
+        for i, (tau, n_app) in enumerate(zip(taus, n_apps)):
+            tv = [float(tau)] * self.Hkv if not hasattr(tau, "__len__") else [float(x) for x in tau]
+            host[i].view(t.float32)[:self.Hkv] = t.tensor(tv, dtype=t.float32)
+            host[i].view(t.int32)[QSAC_MAX_KV_HEADS] = int(n_app)
+        dev = host.cuda()
+        t.cuda.synchronize()
+        return dev
+
+    def copy_on_main(self, dst, src):
+        """dst <- src (device tensors) as an asynchronous copy ordered on the session's main stream."""
+        with self.torch.cuda.stream(self.main):
+            dst.copy_(src, non_blocking=True)
 
     def set_appended(self, n_app: int):
         """Number of valid rows of the append-only buffer from the next step on (the caller has written them)."""

@@ -1,4 +1,5 @@
-"""Builds ``csrc/libqsac.so`` for gfx950 with hipcc (cross-compiles without a GPU)."""
+"""Builds ``csrc/libqsac.so`` (the QSAC step) and ``csrc/libqsac_calib.so`` (measurement aids for the
+benchmark) for gfx950 with hipcc (cross-compiles without a GPU)."""
 from __future__ import annotations
 
 import os
@@ -8,8 +9,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(CSRC, "libqsac.so")
-SOURCES = [os.path.join(CSRC, "qsac.hip")]
-HEADERS = [os.path.join(CSRC, "qsac_kernels.hip.h"), os.path.join(ROOT, "include", "qsac.h")]
+CALIB_LIB = os.path.join(CSRC, "libqsac_calib.so")
+TARGETS = {
+    LIB: ([os.path.join(CSRC, "qsac.hip")],
+          [os.path.join(CSRC, "qsac_kernels.hip.h"), os.path.join(ROOT, "include", "qsac.h")]),
+    CALIB_LIB: ([os.path.join(CSRC, "qsac_calib.hip")], [os.path.join(ROOT, "include", "qsac_calib.h")]),
+}
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -20,13 +25,14 @@ HIPCC_FLAGS = [
 
 
 def build(force: bool = True) -> str:
-    """Compiles the library; with ``force=False`` only when a source is newer than it."""
-    if not force and os.path.exists(LIB):
-        t = os.path.getmtime(LIB)
-        if all(os.path.getmtime(f) <= t for f in SOURCES + HEADERS):
-            return LIB
+    """Compiles both libraries; with ``force=False`` only those older than one of their sources."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    subprocess.check_call([hipcc] + HIPCC_FLAGS + ["-o", LIB] + SOURCES)
+    for lib, (sources, headers) in TARGETS.items():
+        if not force and os.path.exists(lib):
+            t = os.path.getmtime(lib)
+            if all(os.path.getmtime(f) <= t for f in sources + headers):
+                continue
+        subprocess.check_call([hipcc] + HIPCC_FLAGS + ["-o", lib] + sources)
     return LIB
 
 

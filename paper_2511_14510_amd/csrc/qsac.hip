@@ -16,7 +16,8 @@ using namespace qsac;
 
 namespace {
 
-constexpr uint32_t kMagic = 0x51534143u;  // "QSAC"
+constexpr uint32_t kMagic = 0x51534143u;       // "QSAC"
+constexpr uint32_t kGraphMagic = 0x51534147u;  // "QSAG"
 constexpr int kStages = 5;
 const char* const kStageNames[kStages] = {"gate", "score", "select", "fill", "attn"};
 
@@ -121,6 +122,17 @@ struct qsac_ctx {
   double stage_ms[kStages];
   uint64_t stage_calls;
   bool prof_pending;
+  bool broken;  // a HIP call failed in the middle of a step: the caches may be half updated, only a reset clears this
+  // where the fill sources of the last step live (looked up when the pointers change)
+  const void *seen_K_src, *seen_V_src;
+  bool K_src_host, V_src_host;
+};
+
+struct qsac_graph {
+  uint32_t magic;
+  qsac_ctx* ctx;
+  hipGraphExec_t exec;
+  int k;
 };
 
 namespace {
@@ -130,6 +142,16 @@ namespace {
     hipError_t e_ = (expr);           \
     if (e_ != hipSuccess) {           \
       g_last_hip = (int)e_;           \
+      return QSAC_EHIP;               \
+    }                                 \
+  } while (0)
+
+#define HIP_TRY_OR(expr, cleanup)     \
+  do {                                \
+    hipError_t e_ = (expr);           \
+    if (e_ != hipSuccess) {           \
+      g_last_hip = (int)e_;           \
+      cleanup;                        \
       return QSAC_EHIP;               \
     }                                 \
   } while (0)
@@ -145,9 +167,43 @@ int clear_state(qsac_ctx* c) {
   HIP_TRY(hipGetLastError());
   c->k_bound = 0;
   c->steps = 0;
+  c->broken = false;
   for (int i = 0; i < kStages; ++i) c->stage_ms[i] = 0.0;
   c->stage_calls = 0;
   c->prof_pending = false;
+  return QSAC_OK;
+}
+
+// True if `ptr` is host memory mapped into the device (hipHostMalloc); HBM and anything the runtime does not
+// know count as device memory.
+bool is_host_memory(const void* ptr) {
+  hipPointerAttribute_t at;
+  if (hipPointerGetAttributes(&at, ptr) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return at.type == hipMemoryTypeHost;
+}
+
+// The one-workgroup select keeps its candidate list in LDS beyond the default 64 KiB (and the long-context
+// diff its lists): raise the kernels' dynamic LDS limit.  Per device; harmless to repeat.
+int raise_lds_limits() {
+  const int lds_max = std::max((int)(((size_t)(kSmallMaxN / 32) * 3 + 2 * (size_t)kSelectListCap) * sizeof(u32)),
+                               kDiffListMax * 13);
+  const void* fns[] = {(const void*)qsac_select_small_kernel<2, 1024>, (const void*)qsac_select_small_kernel<4, 1024>,
+                       (const void*)qsac_select_small_kernel<8, 1024>, (const void*)qsac_select_small_kernel<16, 1024>,
+                       (const void*)qsac_diff_list_kernel};
+  for (const void* fn : fns) HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_max));
+  return QSAC_OK;
+}
+
+// Eq. (2) weights into the workspace (all 1 when none are given), by a kernel on stream_main.
+int set_importance(qsac_ctx* c, const float* w) {
+  ImportanceArg arg;
+  for (int i = 0; i < c->cfg.n_q_heads; ++i) arg.v[i] = w ? w[i] : 1.f;
+  qsac_set_importance_kernel<<<1, 256, 0, c->s_main>>>(
+      reinterpret_cast<double*>(static_cast<char*>(c->cfg.workspace) + c->L.importance), arg, c->cfg.n_q_heads);
+  HIP_TRY(hipGetLastError());
   return QSAC_OK;
 }
 
@@ -200,6 +256,7 @@ AttnArgs attn_args(const qsac_ctx* c, const qsac_step_args* a, const int* fetch_
   A.out = a->out;
   A.K_app = static_cast<const v4u*>(a->K_app);
   A.V_app = static_cast<const v4u*>(a->V_app);
+  A.dp = reinterpret_cast<const DevParams*>(a->dev_params);
   A.N = c->cfg.n_ctx;
   A.n_app = a->n_app;
   A.app_cap = c->cfg.append_capacity;
@@ -244,129 +301,21 @@ void launch_attn(const qsac_ctx* c, hipStream_t stream, const AttnArgs& A, const
     }                                                           \
   } while (0)
 
-}  // namespace
-
-extern "C" {
-
-size_t qsac_workspace_bytes(const qsac_config* cfg) {
-  if (check_config(cfg) != QSAC_OK) return 0;
-  qsac_ws_layout L;
-  make_layout(cfg, &L);
-  return L.total;
-}
-
-int qsac_workspace_layout(const qsac_config* cfg, qsac_ws_layout* out) {
-  if (!out) return QSAC_ENULL;
-  int rc = check_config(cfg);
-  if (rc != QSAC_OK) return rc;
-  make_layout(cfg, out);
-  return QSAC_OK;
-}
-
-int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
-  if (!out) return QSAC_ENULL;
-  *out = nullptr;
-  int rc = check_config(cfg);
-  if (rc != QSAC_OK) return rc;
-  qsac_ws_layout L;
-  make_layout(cfg, &L);
-  const bool dry = (cfg->flags & QSAC_FLAG_DRY_RUN) != 0;
-  if (!dry) {
-    if (!cfg->workspace) return QSAC_EWORKSPACE;
-    if (reinterpret_cast<uintptr_t>(cfg->workspace) & 255u) return QSAC_EWORKSPACE;
-    if (cfg->workspace_bytes < L.total) return QSAC_EWORKSPACE;
-  }
-  qsac_ctx* c = new (std::nothrow) qsac_ctx();
-  if (!c) return QSAC_EINVAL;
-  c->magic = kMagic;
-  c->cfg = *cfg;
-  c->cfg.q_head_importance = nullptr;  // copied below; the caller's array is not kept
-  c->L = L;
-  c->P = cfg->batch * cfg->n_kv_heads;
-  c->G = cfg->n_q_heads / cfg->n_kv_heads;
-  c->dry = dry;
-  c->small = cfg->n_ctx <= kSmallMaxN;
-  c->s_main = static_cast<hipStream_t>(cfg->stream_main);
-  c->s_side = static_cast<hipStream_t>(cfg->stream_side);
-  c->fill_kernel = (cfg->flags & QSAC_FLAG_FILL_KERNEL) != 0;
-  c->overlap = cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main && !(cfg->flags & QSAC_FLAG_SERIAL);
-  c->profile = (cfg->flags & QSAC_FLAG_PROFILE) != 0;
-  if (c->profile) c->overlap = false;  // stage times are taken on one stream
-  c->k_bound = 0;
-  c->steps = 0;
-  c->ev_sel = c->ev_fill = nullptr;
-  for (auto& e : c->prof) e = nullptr;
-  if (dry) {
-    *out = c;
-    return QSAC_OK;
-  }
-  auto fail = [&](int code) {
-    qsac_free(c);
-    return code;
-  };
-  if (hipEventCreateWithFlags(&c->ev_sel, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&c->ev_fill, hipEventDisableTiming) != hipSuccess) {
-    g_last_hip = (int)hipGetLastError();
-    return fail(QSAC_EHIP);
-  }
-  if (c->profile)
-    for (auto& e : c->prof)
-      if (hipEventCreate(&e) != hipSuccess) {
-        g_last_hip = (int)hipGetLastError();
-        return fail(QSAC_EHIP);
-      }
-  // Eq. (2) weights, widened to fp64 on the host; a synchronous copy, so the staging buffer can go.
-  {
-    double* w = static_cast<double*>(std::malloc(sizeof(double) * (size_t)cfg->n_q_heads));
-    if (!w) return fail(QSAC_EINVAL);
-    for (int i = 0; i < cfg->n_q_heads; ++i) w[i] = cfg->q_head_importance ? (double)cfg->q_head_importance[i] : 1.0;
-    hipError_t e = hipMemcpy(static_cast<char*>(cfg->workspace) + L.importance, w,
-                             sizeof(double) * (size_t)cfg->n_q_heads, hipMemcpyHostToDevice);
-    std::free(w);
-    if (e != hipSuccess) {
-      g_last_hip = (int)e;
-      return fail(QSAC_EHIP);
-    }
-  }
-  {
-    // the one-workgroup select keeps its candidate list in LDS beyond the default 64 KiB
-    // (and the long-context diff its lists)
-    const int lds_max = std::max((int)(((size_t)(kSmallMaxN / 32) * 3 + 2 * (size_t)kSelectListCap) * sizeof(u32)),
-                                 kDiffListMax * 13);
-    const void* fns[] = {(const void*)qsac_select_small_kernel<2, 1024>, (const void*)qsac_select_small_kernel<4, 1024>,
-                         (const void*)qsac_select_small_kernel<8, 1024>, (const void*)qsac_select_small_kernel<16, 1024>,
-                         (const void*)qsac_diff_list_kernel};
-    for (const void* fn : fns) {
-      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_max);
-      if (e != hipSuccess) {
-        g_last_hip = (int)e;
-        return fail(QSAC_EHIP);
-      }
-    }
-  }
-  rc = clear_state(c);
-  if (rc != QSAC_OK) return fail(rc);
-  *out = c;
-  return QSAC_OK;
-}
-
-int qsac_reset(qsac_ctx* c) {
-  if (!c || c->magic != kMagic) return QSAC_ESTATE;
-  c->k_bound = 0;
-  c->steps = 0;
-  if (c->dry) return QSAC_OK;
-  return clear_state(c);
-}
-
-int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
+// Everything qsac_step checks before anything is enqueued.
+int validate_step(const qsac_ctx* c, const qsac_step_args* a) {
   if (!c || c->magic != kMagic) return QSAC_ESTATE;
   if (!a) return QSAC_ENULL;
   if (!a->q || !a->K_dev || !a->K_src || !a->V_src || !a->K_slots || !a->V_slots || !a->slot_idx || !a->prev_q ||
-      !a->tau || !a->out || !a->topk_idx || !a->hit_mask || !a->reuse_flags)
+      !a->out || !a->topk_idx || !a->hit_mask || !a->reuse_flags)
     return QSAC_ENULL;
-  if (a->n_tau != 1 && a->n_tau != c->cfg.n_kv_heads) return QSAC_EINVAL;
-  for (int i = 0; i < a->n_tau; ++i)
-    if (std::isnan(a->tau[i])) return QSAC_EINVAL;
+  if (a->dev_params) {
+    if (!aligned16(a->dev_params)) return QSAC_EALIGN;  // tau and n_app come from the device at run time
+  } else {
+    if (!a->tau) return QSAC_ENULL;
+    if (a->n_tau != 1 && a->n_tau != c->cfg.n_kv_heads) return QSAC_EINVAL;
+    for (int i = 0; i < a->n_tau; ++i)
+      if (std::isnan(a->tau[i])) return QSAC_EINVAL;
+  }
   if (a->k < 1 || a->k > c->cfg.k_max) return QSAC_ERANGE;
   if (c->k_bound != 0 && a->k != c->k_bound) return QSAC_ESTATE;
   const void* al[] = {a->q, a->K_dev, a->K_src, a->V_src, a->K_slots, a->V_slots, a->slot_idx, a->prev_q, a->out, a->topk_idx};
@@ -385,9 +334,25 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     for (int h = 0; h < c->cfg.n_kv_heads; ++h)
       if (a->res_slot[h] < -1 || a->res_slot[h] >= a->n_res) return QSAC_ERANGE;
   }
-  c->k_bound = a->k;
-  c->steps += 1;
-  if (c->dry) return QSAC_OK;
+  if (c->broken) return QSAC_ESTATE;
+  return QSAC_OK;
+}
+
+// Looks up, when the pointers change, whether the fill sources are host memory (for the byte counters).
+void note_fill_sources(qsac_ctx* c, const qsac_step_args* a) {
+  if (a->K_src != c->seen_K_src) {
+    c->K_src_host = is_host_memory(a->K_src);
+    c->seen_K_src = a->K_src;
+  }
+  if (a->V_src != c->seen_V_src) {
+    c->V_src_host = is_host_memory(a->V_src);
+    c->seen_V_src = a->V_src;
+  }
+}
+
+// Enqueues the launches of one step (also what a graph capture records).  QSAC_EHIP if a HIP call fails,
+// possibly after part of the step has been enqueued.
+int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
 
   const qsac_ws_layout& L = c->L;
   char* ws = static_cast<char*>(c->cfg.workspace);
@@ -421,14 +386,16 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     if (c->profile) (void)hipEventRecord(c->prof[i], sm);
   };
 
+  const DevParams* dp = reinterpret_cast<const DevParams*>(a->dev_params);
   TauArg tau;
-  for (int h = 0; h < Hkv; ++h) tau.v[h] = a->tau[a->n_tau == 1 ? 0 : h];
+  for (int h = 0; h < Hkv; ++h) tau.v[h] = dp ? 0.f : a->tau[a->n_tau == 1 ? 0 : h];
   FillSrc src;
   src.K_src = static_cast<const v4u*>(a->K_src);
   src.V_src = static_cast<const v4u*>(a->V_src);
   src.K_res = static_cast<const v4u*>(a->K_dev);
   src.V_res = static_cast<const v4u*>(a->V_res);
   src.n_res = a->res_slot ? a->n_res : 0;
+  src.host_row_bytes = 256 * ((int)c->K_src_host + (int)c->V_src_host);
   for (int h = 0; h < 64; ++h) src.slot[h] = (a->res_slot && h < Hkv) ? a->res_slot[h] : -1;
 
   // 1. gate (+ label update on a miss)
@@ -437,12 +404,12 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
     qsac_gate_kernel<0><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
                                            a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max,
-                                           !c->small);
+                                           !c->small, dp);
   else
     qsac_gate_kernel<1><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
                                            a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max,
-                                           !c->small);
+                                           !c->small, dp);
   const int rows = attn_rows(P, k + a->n_app);
   const int n_splits = (k + a->n_app + rows - 1) / rows;
   dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
@@ -564,6 +531,180 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   return QSAC_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+size_t qsac_workspace_bytes(const qsac_config* cfg) {
+  if (check_config(cfg) != QSAC_OK) return 0;
+  qsac_ws_layout L;
+  make_layout(cfg, &L);
+  return L.total;
+}
+
+int qsac_workspace_layout(const qsac_config* cfg, qsac_ws_layout* out) {
+  if (!out) return QSAC_ENULL;
+  int rc = check_config(cfg);
+  if (rc != QSAC_OK) return rc;
+  make_layout(cfg, out);
+  return QSAC_OK;
+}
+
+int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
+  if (!out) return QSAC_ENULL;
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc != QSAC_OK) return rc;
+  qsac_ws_layout L;
+  make_layout(cfg, &L);
+  const bool dry = (cfg->flags & QSAC_FLAG_DRY_RUN) != 0;
+  if (!dry) {
+    if (!cfg->workspace) return QSAC_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(cfg->workspace) & 255u) return QSAC_EWORKSPACE;
+    if (cfg->workspace_bytes < L.total) return QSAC_EWORKSPACE;
+  }
+  qsac_ctx* c = new (std::nothrow) qsac_ctx();
+  if (!c) return QSAC_EINVAL;
+  c->magic = kMagic;
+  c->cfg = *cfg;
+  c->cfg.q_head_importance = nullptr;  // copied below; the caller's array is not kept
+  c->L = L;
+  c->P = cfg->batch * cfg->n_kv_heads;
+  c->G = cfg->n_q_heads / cfg->n_kv_heads;
+  c->dry = dry;
+  c->small = cfg->n_ctx <= kSmallMaxN;
+  c->s_main = static_cast<hipStream_t>(cfg->stream_main);
+  c->s_side = static_cast<hipStream_t>(cfg->stream_side);
+  c->fill_kernel = (cfg->flags & QSAC_FLAG_FILL_KERNEL) != 0;
+  c->overlap = cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main && !(cfg->flags & QSAC_FLAG_SERIAL);
+  c->profile = (cfg->flags & QSAC_FLAG_PROFILE) != 0;
+  if (c->profile) c->overlap = false;  // stage times are taken on one stream
+  c->k_bound = 0;
+  c->steps = 0;
+  c->broken = false;
+  c->seen_K_src = c->seen_V_src = nullptr;
+  c->K_src_host = c->V_src_host = false;
+  c->ev_sel = c->ev_fill = nullptr;
+  for (auto& e : c->prof) e = nullptr;
+  if (dry) {
+    *out = c;
+    return QSAC_OK;
+  }
+  auto fail = [&](int code) {
+    qsac_free(c);
+    return code;
+  };
+  if (hipEventCreateWithFlags(&c->ev_sel, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_fill, hipEventDisableTiming) != hipSuccess) {
+    g_last_hip = (int)hipGetLastError();
+    return fail(QSAC_EHIP);
+  }
+  if (c->profile)
+    for (auto& e : c->prof)
+      if (hipEventCreate(&e) != hipSuccess) {
+        g_last_hip = (int)hipGetLastError();
+        return fail(QSAC_EHIP);
+      }
+  rc = raise_lds_limits();
+  if (rc != QSAC_OK) return fail(rc);
+  rc = set_importance(c, cfg->q_head_importance);
+  if (rc != QSAC_OK) return fail(rc);
+  rc = clear_state(c);
+  if (rc != QSAC_OK) return fail(rc);
+  *out = c;
+  return QSAC_OK;
+}
+
+int qsac_reset(qsac_ctx* c) {
+  if (!c || c->magic != kMagic) return QSAC_ESTATE;
+  if (c->dry) {
+    c->k_bound = 0;
+    c->steps = 0;
+    return QSAC_OK;
+  }
+  return clear_state(c);
+}
+
+int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
+  if (!c || c->magic != kMagic) return QSAC_ESTATE;
+  int rc = validate_step(c, a);
+  if (rc != QSAC_OK) return rc;
+  if (!c->dry) {
+    note_fill_sources(c, a);
+    rc = enqueue_step(c, a);
+    if (rc != QSAC_OK) {
+      c->broken = true;  // part of the step may be enqueued: labels and slots can disagree until a reset
+      return rc;
+    }
+  }
+  c->k_bound = a->k;
+  c->steps += 1;
+  return QSAC_OK;
+}
+
+int qsac_graph_capture(qsac_ctx* c, const qsac_step_args* a, qsac_graph** out) {
+  if (!out) return QSAC_ENULL;
+  *out = nullptr;
+  if (!c || c->magic != kMagic) return QSAC_ESTATE;
+  if (c->dry || c->profile) return QSAC_ESTATE;
+  int rc = validate_step(c, a);
+  if (rc != QSAC_OK) return rc;
+  if (!a->dev_params) return QSAC_ENULL;
+  note_fill_sources(c, a);
+  qsac_graph* g = new (std::nothrow) qsac_graph();
+  if (!g) return QSAC_EINVAL;
+  HIP_TRY_OR(hipStreamBeginCapture(c->s_main, hipStreamCaptureModeThreadLocal), delete g);
+  rc = enqueue_step(c, a);
+  hipGraph_t graph = nullptr;
+  const hipError_t e_end = hipStreamEndCapture(c->s_main, &graph);  // always leave capture mode
+  if (rc == QSAC_OK && e_end != hipSuccess) {
+    g_last_hip = (int)e_end;
+    rc = QSAC_EHIP;
+  }
+  if (rc == QSAC_OK) {
+    const hipError_t e_inst = hipGraphInstantiate(&g->exec, graph, nullptr, nullptr, 0);
+    if (e_inst != hipSuccess) {
+      g_last_hip = (int)e_inst;
+      rc = QSAC_EHIP;
+    }
+  }
+  if (graph) (void)hipGraphDestroy(graph);
+  if (rc != QSAC_OK) {
+    (void)hipGetLastError();
+    delete g;
+    return rc;  // nothing ran: the context is as it was
+  }
+  g->magic = kGraphMagic;
+  g->ctx = c;
+  g->k = a->k;
+  *out = g;
+  return QSAC_OK;
+}
+
+int qsac_graph_launch(qsac_graph* g) {
+  if (!g || g->magic != kGraphMagic) return QSAC_ESTATE;
+  qsac_ctx* c = g->ctx;
+  if (!c || c->magic != kMagic || c->broken) return QSAC_ESTATE;
+  if (c->k_bound != 0 && c->k_bound != g->k) return QSAC_ESTATE;
+  const hipError_t e = hipGraphLaunch(g->exec, c->s_main);
+  if (e != hipSuccess) {
+    g_last_hip = (int)e;
+    c->broken = true;
+    return QSAC_EHIP;
+  }
+  c->k_bound = g->k;
+  c->steps += 1;
+  return QSAC_OK;
+}
+
+int qsac_graph_free(qsac_graph* g) {
+  if (!g || g->magic != kGraphMagic) return QSAC_ESTATE;
+  (void)hipGraphExecDestroy(g->exec);
+  g->magic = 0;
+  delete g;
+  return QSAC_OK;
+}
+
 int qsac_get_stats(qsac_ctx* c, qsac_stats* out) {
   if (!c || c->magic != kMagic) return QSAC_ESTATE;
   if (!out) return QSAC_ENULL;
@@ -579,6 +720,8 @@ int qsac_get_stats(qsac_ctx* c, qsac_stats* out) {
   out->slot_misses = dev[4];
   out->resident_rows = dev[5];
   out->guided_selects = dev[6];
+  out->bytes_filled_host = dev[7];
+  out->bytes_filled_dev = 512ull * dev[4] - dev[7];
   return QSAC_OK;
 }
 
@@ -613,10 +756,10 @@ const char* qsac_strerror(int code) {
     case QSAC_OK: return "ok";
     case QSAC_EINVAL: return "invalid value in an argument";
     case QSAC_ENULL: return "required pointer is NULL";
-    case QSAC_ERANGE: return "size or count out of range";
+    case QSAC_ERANGE: return "size or count out of range (n_ctx is limited to 2^20, G to 8, n_kv_heads to 64)";
     case QSAC_EWORKSPACE: return "workspace missing, misaligned or too small";
     case QSAC_EHIP: return "HIP runtime call failed";
-    case QSAC_ESTATE: return "bad handle or call out of order";
+    case QSAC_ESTATE: return "bad handle, call out of order, or the context needs qsac_reset after a failed step";
     case QSAC_EALIGN: return "pointer is not 16-byte aligned";
     default: return "unknown error";
   }
@@ -645,25 +788,6 @@ int qsac_reuse_difficulty(const float* tau, const float* avg_sim, int32_t n, flo
   if (n < 0) return QSAC_ERANGE;
   if (!(eps > 0.f) || !std::isfinite(eps)) return QSAC_EINVAL;
   for (int i = 0; i < n; ++i) d_out[i] = (float)((double)tau[i] - ((double)avg_sim[i] - (double)eps));
-  return QSAC_OK;
-}
-
-int qsac_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
-  if (!dst || !src) return QSAC_ENULL;
-  if (!aligned16(dst) || !aligned16(src) || (bytes & 15u)) return QSAC_EALIGN;
-  if (bytes == 0) return QSAC_OK;
-  qsac_copy_kernel<<<4096, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<v4u*>(dst), static_cast<const v4u*>(src), bytes / 16);
-  HIP_TRY(hipGetLastError());
-  return QSAC_OK;
-}
-
-int qsac_calibration_read(const void* src, size_t bytes, void* sink, void* stream) {
-  if (!src || !sink) return QSAC_ENULL;
-  if (!aligned16(src) || (bytes & 15u) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return QSAC_EALIGN;
-  if (bytes == 0) return QSAC_OK;
-  qsac_read_kernel<<<2048, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const v4u*>(src), bytes / 16,
-                                                                      static_cast<u32*>(sink));
-  HIP_TRY(hipGetLastError());
   return QSAC_OK;
 }
 

@@ -66,7 +66,16 @@ struct FillSrc {
   const v4u* K_res;
   const v4u* V_res;
   int n_res;
+  int host_row_bytes;    // bytes of a (K row, V row) pair of a non-resident head that come from host memory: 0, 256 or 512
   signed char slot[64];  // per KV head: index in V_res, -1 if not resident
+};
+
+// Per-step scalars read from device memory when a step is replayed from a captured graph (mirror of
+// qsac_dev_params in qsac.h).
+struct DevParams {
+  float tau[64];
+  int n_app;
+  int reserved[3];
 };
 __device__ __forceinline__ void fill_rows_of(const FillSrc& f, int p, int Hkv, int64_t N, const v4u*& Ks,
                                              const v4u*& Vs) {
@@ -299,7 +308,7 @@ __global__ __launch_bounds__(256) void qsac_gate_kernel(
     TauArg tau, const u32* __restrict__ valid, const int* __restrict__ set_sorted, int* __restrict__ topk_idx,
     uint8_t* __restrict__ hit_mask, uint8_t* __restrict__ reuse_flags, float* __restrict__ sim_out,
     int* __restrict__ miss_count, u32* __restrict__ hist, u64* __restrict__ stats, int Hq, int Hkv, int G,
-    int k, int k_max, bool clear_hist) {
+    int k, int k_max, bool clear_hist, const DevParams* __restrict__ dp) {
   const int p = blockIdx.x;
   const int b = p / Hkv, h = p % Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -311,6 +320,7 @@ __global__ __launch_bounds__(256) void qsac_gate_kernel(
   u32* pq32 = reinterpret_cast<u32*>(prev_q) + head0 * (kD / 2);
   // everything the decision needs is requested up front, so the kernel pays one memory round trip
   const u32 was_valid = valid[p];
+  const float tau_h = dp ? dp->tau[h] : tau.v[h];
   if (threadIdx.x < G) s_imp[threadIdx.x] = importance[h * G + threadIdx.x];
 
   for (int g = wave; g < G; g += 4) {
@@ -339,7 +349,7 @@ __global__ __launch_bounds__(256) void qsac_gate_kernel(
       den += w / s;
     }
     double agg = nonpos ? -1.0 : num / den;
-    int reuse = (was_valid != 0) && (agg >= (double)tau.v[h]);
+    int reuse = (was_valid != 0) && (agg >= (double)tau_h);
     s_reuse = reuse;
     reuse_flags[p] = (uint8_t)reuse;
     atomicAdd(&stats[reuse ? 1 : 2], 1ull);
@@ -847,7 +857,10 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_list_kernel(
     valid[p] = 1;
     atomicAdd(&stats[3], (u64)(k - m));
     atomicAdd(&stats[4], (u64)m);
-    if (src.slot[p % Hkv] >= 0) atomicAdd(&stats[5], (u64)m);
+    if (src.slot[p % Hkv] >= 0)
+      atomicAdd(&stats[5], (u64)m);
+    else if (src.host_row_bytes)
+      atomicAdd(&stats[7], (u64)m * (u64)src.host_row_bytes);
   }
 }
 
@@ -870,7 +883,8 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
                                             int* __restrict__ tk, uint8_t* __restrict__ hm, int* __restrict__ ms,
                                             int* __restrict__ mt, int* __restrict__ ft,
                                             int* __restrict__ miss_count_p, u32* __restrict__ valid_p,
-                                            u64* __restrict__ stats, bool resident, int* s_wave) {
+                                            u64* __restrict__ stats, bool resident, int host_row_bytes,
+                                            int* s_wave) {
   constexpr int NW = NT / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // Wave w owns the contiguous words [wb, we); lane l takes words wb + l, wb + l + 64, ... (at most
@@ -1038,7 +1052,10 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
     *valid_p = 1;
     atomicAdd(&stats[3], (u64)(k - m));
     atomicAdd(&stats[4], (u64)m);
-    if (resident) atomicAdd(&stats[5], (u64)m);
+    if (resident)
+      atomicAdd(&stats[5], (u64)m);
+    else if (host_row_bytes)
+      atomicAdd(&stats[7], (u64)m * (u64)host_row_bytes);
   }
 }
 
@@ -1063,7 +1080,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
                             set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
                             miss_slot + (size_t)p * k_max, miss_tok + (size_t)p * k_max,
                             fetch_tok + (size_t)p * k_max, miss_count + p, valid + p, stats,
-                            src.slot[p % Hkv] >= 0, s_wave);
+                            src.slot[p % Hkv] >= 0, src.host_row_bytes, s_wave);
 }
 
 // OR over aligned groups of 8 lanes (DPP: xor 1, xor 2, then mirror within each half row).
@@ -1254,7 +1271,7 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
                              A.set_sorted + (size_t)p * k_max, A.topk_idx + (size_t)p * k, A.hit_mask + (size_t)p * k,
                              A.miss_slot + (size_t)p * k_max, A.miss_tok + (size_t)p * k_max,
                              A.fetch_tok + (size_t)p * k_max, A.miss_count + p, A.valid + p, A.stats,
-                             src.slot[p % A.Hkv] >= 0, s_wave);
+                             src.slot[p % A.Hkv] >= 0, src.host_row_bytes, s_wave);
 }
 
 template <int VPT, int NT>
@@ -1360,6 +1377,7 @@ struct AttnArgs {
   float* out;
   const v4u* K_app;
   const v4u* V_app;
+  const DevParams* dp;  // nullptr, or where the number of valid append-buffer rows is read from (then n_app bounds it)
   int64_t N;
   int n_app, app_cap, Hq, Hkv, k, k_max, rows, n_splits, max_splits, which;
 };
@@ -1392,7 +1410,10 @@ __device__ __forceinline__ void attn_body(const AttnArgs& A, const FillSrc& src,
   const v4u* __restrict__ K_app = A.K_app;
   const v4u* __restrict__ V_app = A.V_app;
   const int64_t N = A.N;
-  const int n_app = A.n_app, app_cap = A.app_cap, Hq = A.Hq, Hkv = A.Hkv, k = A.k, k_max = A.k_max, rows = A.rows,
+  // a replayed step reads the row count of the append-only buffer from device memory; the launch is sized for
+  // A.n_app rows, and the splits past the valid rows contribute empty partials
+  const int n_app = A.dp ? max(0, min(A.dp->n_app, A.n_app)) : A.n_app;
+  const int app_cap = A.app_cap, Hq = A.Hq, Hkv = A.Hkv, k = A.k, k_max = A.k_max, rows = A.rows,
             n_splits = A.n_splits, max_splits = A.max_splits;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = lane & 15, quarter = lane >> 4;
@@ -1688,32 +1709,18 @@ __global__ __launch_bounds__(512) void qsac_combine_kernel(const float* __restri
   out[((size_t)b * Hq + (size_t)h * G + g) * kD + d] = A / L;
 }
 
+// Eq. (2) weights s_j of the query heads, widened to fp64 where the gate reads them.  They travel as a kernel
+// argument, so that setting them needs neither a copy nor a staging buffer.
+struct ImportanceArg {
+  float v[512];  // QSAC_MAX_KV_HEADS * QSAC_MAX_GROUP query heads at most
+};
+__global__ __launch_bounds__(256) void qsac_set_importance_kernel(double* __restrict__ importance, ImportanceArg w, int n) {
+  for (int i = threadIdx.x; i < n; i += 256) importance[i] = (double)w.v[i];
+}
+
 // Clears `n` 32-bit words (used instead of a memset node so that the step can be captured in a graph).
 __global__ __launch_bounds__(256) void qsac_zero_kernel(u32* __restrict__ ptr, size_t n) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) ptr[i] = 0;
-}
-
-// Plain 16-byte-per-lane copy of n vectors: the known-size kernel that hardware counters are
-// calibrated against.
-__global__ __launch_bounds__(256) void qsac_copy_kernel(v4u* __restrict__ dst, const v4u* __restrict__ src, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
-}
-
-// Read-only counterpart: every workgroup reads a contiguous span, eight non-temporal 16-byte loads
-// per thread in flight; what a launch of a given size can reach with no arithmetic at all.  The
-// XOR of everything read goes to `sink` only if it equals a magic value, so the loads stay.
-__global__ __launch_bounds__(256) void qsac_read_kernel(const v4u* __restrict__ src, size_t n, u32* __restrict__ sink) {
-  const size_t span = (n + gridDim.x - 1) / gridDim.x;
-  const size_t b = (size_t)blockIdx.x * span, e = b + span < n ? b + span : n;
-  u32 acc = 0;
-  for (size_t i = b + threadIdx.x; i < e; i += 256 * 8) {
-    v4u v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = (i + u * 256 < e) ? __builtin_nontemporal_load(src + i + u * 256) : v4u{0, 0, 0, 0};
-#pragma unroll
-    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
-  }
-  if (acc == 0x9e3779b9u) sink[0] = acc;
 }
 
 }  // namespace qsac

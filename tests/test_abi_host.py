@@ -20,13 +20,23 @@ def lib():
     return Q.load()
 
 
-def test_exports_every_declared_symbol(lib):
-    text = open(os.path.join(ROOT, "include", "qsac.h")).read()
+def _declared(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(qsac_[a-z_]+)\s*\(", text))
+    return set(re.findall(r"\b(qsac_[a-z_]+)\s*\(", text))
+
+
+def test_exports_every_declared_symbol(lib):
+    declared = _declared("qsac.h")
     assert declared == set(Q.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
+    # the measurement aids live in a library of their own and are not part of the product library
+    calib = Q.load_calib()
+    assert _declared("qsac_calib.h") == set(Q.CALIB_EXPORTS)
+    for name in Q.CALIB_EXPORTS:
+        assert hasattr(calib, name), name
+        assert not hasattr(lib, name), name
 
 
 def test_struct_sizes_match_the_header(lib):
@@ -34,14 +44,15 @@ def test_struct_sizes_match_the_header(lib):
     src = r'''
     #include "qsac.h"
     #include <stdio.h>
-    int main(void){ printf("%zu %zu %zu %zu\n", sizeof(qsac_config), sizeof(qsac_ws_layout), sizeof(qsac_step_args), sizeof(qsac_stats)); return 0; }
+    int main(void){ printf("%zu %zu %zu %zu %zu\n", sizeof(qsac_config), sizeof(qsac_ws_layout), sizeof(qsac_step_args), sizeof(qsac_stats), sizeof(qsac_dev_params)); return 0; }
     '''
     import subprocess, tempfile
     with tempfile.TemporaryDirectory() as d:
         open(os.path.join(d, "s.c"), "w").write(src)
         subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), "-o", os.path.join(d, "s"), os.path.join(d, "s.c")])
         sizes = [int(x) for x in subprocess.check_output([os.path.join(d, "s")]).split()]
-    assert sizes == [C.sizeof(Q.qsac_config), C.sizeof(Q.qsac_ws_layout), C.sizeof(Q.qsac_step_args), C.sizeof(Q.qsac_stats)]
+    assert sizes == [C.sizeof(Q.qsac_config), C.sizeof(Q.qsac_ws_layout), C.sizeof(Q.qsac_step_args), C.sizeof(Q.qsac_stats),
+                     C.sizeof(Q.qsac_dev_params)]
 
 
 def test_workspace_size_and_layout(lib):
@@ -96,7 +107,7 @@ def test_workspace_checks_without_dry_run(lib):
 def _args(**over):
     a = Q.qsac_step_args()
     for f, _ in Q.qsac_step_args._fields_:
-        if f not in ("tau", "n_tau", "k", "V_res", "res_slot", "n_res", "K_app", "V_app", "n_app"):
+        if f not in ("tau", "n_tau", "k", "V_res", "res_slot", "n_res", "K_app", "V_app", "n_app", "dev_params"):
             setattr(a, f, 0x10000)
     tau = (C.c_float * 2)(0.9, 0.8)
     a._keep = tau
@@ -137,8 +148,18 @@ def test_step_validation_on_a_dry_run_context(lib):
     assert step(_args(k=128)) == Q.QSAC_ESTATE                     # k changed without a reset
     Q.qsac_reset(ctx)
     assert step(_args(k=128)) == Q.QSAC_OK
+    # per-step scalars in device memory: tau may then be absent; the block must be aligned
+    assert step(_args(k=128, dev_params=0x50000, tau=C.POINTER(C.c_float)(), n_tau=0)) == Q.QSAC_OK
+    assert step(_args(k=128, dev_params=0x50004)) == Q.QSAC_EALIGN
     st = Q.qsac_get_stats(ctx)
-    assert st["steps"] == 1 and st["reuse_heads"] == 0
+    assert st["steps"] == 2 and st["bytes_filled_host"] == 0 and st["bytes_filled_dev"] == 0   # failed calls do not count
+    # a graph needs a context that runs on a device
+    g = C.c_void_p()
+    assert lib.qsac_graph_capture(ctx, C.byref(_args(k=128, dev_params=0x50000)), C.byref(g)) == Q.QSAC_ESTATE
+    assert lib.qsac_graph_capture(ctx, C.byref(_args(k=128)), None) == Q.QSAC_ENULL
+    assert lib.qsac_graph_launch(None) == Q.QSAC_ESTATE and lib.qsac_graph_free(None) == Q.QSAC_ESTATE
+    st = Q.qsac_get_stats(ctx)
+    assert st["steps"] == 2 and st["reuse_heads"] == 0
     Q.qsac_free(ctx)
     assert lib.qsac_free(None) == Q.QSAC_ESTATE
     assert lib.qsac_reset(None) == Q.QSAC_ESTATE
@@ -209,8 +230,9 @@ def test_sink_recent_and_append_validation(lib):
         assert Q.qsac_workspace_bytes(bad) == 0
 
 
-def test_calibration_entry_points_validate_before_touching_a_device(lib):
+def test_calibration_entry_points_validate_before_touching_a_device():
     # NULL and misaligned arguments are turned down on the host; nothing is launched
+    lib = Q.load_calib()
     assert lib.qsac_calibration_copy(None, None, 256, None) == Q.QSAC_ENULL
     assert lib.qsac_calibration_read(None, 256, None, None) == Q.QSAC_ENULL
     assert lib.qsac_calibration_copy(4096, 8192, 24, None) == Q.QSAC_EALIGN      # size not a multiple of 16
