@@ -21,16 +21,21 @@ import numpy as np
 F16, BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qsac_oracle.c")
-_LIB = os.path.join(_HERE, "libqsac_oracle.so")
+# QSAC_ORACLE_SANITIZE=1 selects a build with AddressSanitizer and UndefinedBehaviorSanitizer (host code only;
+# the process then needs the sanitizer runtime preloaded, see tests/test_oracle_sanitized.py).
+SANITIZE = os.environ.get("QSAC_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libqsac_oracle_san.so" if SANITIZE else "libqsac_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (fp64, OpenMP over independent pairs)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        extra = ["-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                 "-fno-omit-frame-pointer"] if SANITIZE else []
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-             "-D_GNU_SOURCE", "-o", _LIB, _SRC, "-lm"])
+            ["gcc", "-O1" if SANITIZE else "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+             "-D_GNU_SOURCE"] + extra + ["-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 

@@ -13,7 +13,9 @@ Recipe
          8 before rounding once to fp16 / bf16.
   q_t    q_0 = normalize(e_0); q_t = normalize(rho q_{t-1} + sqrt(1-rho^2) e_t)
          with e_t ~ N(0, I/D), so cos(q_t, q_{t-1}) is rho up to a jitter of a
-         few hundredths; every query head runs its own chain.  ``exact=True``
+         few hundredths; every query head runs its own chain (the low-similarity
+         workload draws one rho per KV head from U[0.3, 0.99], shared by the
+         query heads of the group).  ``exact=True``
          orthogonalises e_t against q_{t-1} and normalises it, which makes the
          cosine exactly rho before rounding.  ``q_norm`` rescales the emitted
          queries (the gate and the ranking do not depend on it; a large norm
@@ -45,7 +47,7 @@ class Workload:
     dtype: str
     steps: int
     tau: float = 0.9
-    rho: float = 0.95          # scalar; rho_range overrides it per query head
+    rho: float = 0.95          # scalar; rho_range overrides it with one value per KV head
     rho_range: tuple | None = None
     host_k: bool = False       # fill source of K rows lives in pinned host memory
     host_v: bool = False       # fill source of V rows lives in pinned host memory
@@ -133,13 +135,21 @@ class QueryChain:
         return self._q * self.q_norm
 
 
-def per_head_rho(Hq: int, lo: float, hi: float, seed: int) -> np.ndarray:
+def per_head_rho(Hkv: int, lo: float, hi: float, seed: int) -> np.ndarray:
+    """One correlation per KV head, uniform over [lo, hi]: the Hkv equally spaced quantiles from lo to hi (both
+    ends included), handed to the heads in a seeded random order.  Eight independent draws can miss a whole
+    part of the range (with the default seed: everything above 0.84), and a threshold sweep over 0.8 - 0.95
+    would then see no head that ever reuses; the quantiles cover the range whatever the seed."""
     rng = np.random.Generator(np.random.Philox(key=[seed, 0x51D0]))
-    return rng.uniform(lo, hi, size=Hq)
+    grid = np.linspace(lo, hi, Hkv) if Hkv > 1 else np.array([0.5 * (lo + hi)])
+    return grid[rng.permutation(Hkv)]
 
 
 def chain_for(w: Workload, **kw) -> QueryChain:
-    rho = per_head_rho(w.Hq, *w.rho_range, w.seed) if w.rho_range else w.rho
+    """The query chains of a workload.  With ``rho_range`` every KV head draws its own correlation and the
+    query heads of its group share it (each still runs its own chain): the cache, its gate and its reuse
+    rate are per KV head, so this is what makes reuse rates differ from head to head."""
+    rho = np.repeat(per_head_rho(w.Hkv, *w.rho_range, w.seed), w.G) if w.rho_range else w.rho
     return QueryChain(w.B, w.Hq, w.D, rho, w.seed, **kw)
 
 
