@@ -301,6 +301,34 @@ void launch_attn(const qsac_ctx* c, hipStream_t stream, const AttnArgs& A, const
     }                                                           \
   } while (0)
 
+// The host-side fields of a context for `cfg` (no events yet, nothing enqueued).
+void fill_ctx(qsac_ctx* c, const qsac_config* cfg, const qsac_ws_layout& L) {
+  c->magic = kMagic;
+  c->cfg = *cfg;
+  c->cfg.q_head_importance = nullptr;  // handed to the device at set-up; the caller's array is not kept
+  c->L = L;
+  c->P = cfg->batch * cfg->n_kv_heads;
+  c->G = cfg->n_q_heads / cfg->n_kv_heads;
+  c->dry = (cfg->flags & QSAC_FLAG_DRY_RUN) != 0;
+  c->small = cfg->n_ctx <= kSmallMaxN;
+  c->s_main = static_cast<hipStream_t>(cfg->stream_main);
+  c->s_side = static_cast<hipStream_t>(cfg->stream_side);
+  c->fill_kernel = (cfg->flags & QSAC_FLAG_FILL_KERNEL) != 0;
+  c->overlap = cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main && !(cfg->flags & QSAC_FLAG_SERIAL);
+  c->profile = (cfg->flags & QSAC_FLAG_PROFILE) != 0;
+  if (c->profile) c->overlap = false;  // stage times are taken on one stream
+  c->k_bound = 0;
+  c->steps = 0;
+  c->broken = false;
+  c->seen_K_src = c->seen_V_src = nullptr;
+  c->K_src_host = c->V_src_host = false;
+  c->ev_sel = c->ev_fill = nullptr;
+  for (auto& e : c->prof) e = nullptr;
+  for (int i = 0; i < kStages; ++i) c->stage_ms[i] = 0.0;
+  c->stage_calls = 0;
+  c->prof_pending = false;
+}
+
 // Everything qsac_step checks before anything is enqueued.
 int validate_step(const qsac_ctx* c, const qsac_step_args* a) {
   if (!c || c->magic != kMagic) return QSAC_ESTATE;
@@ -565,27 +593,7 @@ int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
   }
   qsac_ctx* c = new (std::nothrow) qsac_ctx();
   if (!c) return QSAC_EINVAL;
-  c->magic = kMagic;
-  c->cfg = *cfg;
-  c->cfg.q_head_importance = nullptr;  // copied below; the caller's array is not kept
-  c->L = L;
-  c->P = cfg->batch * cfg->n_kv_heads;
-  c->G = cfg->n_q_heads / cfg->n_kv_heads;
-  c->dry = dry;
-  c->small = cfg->n_ctx <= kSmallMaxN;
-  c->s_main = static_cast<hipStream_t>(cfg->stream_main);
-  c->s_side = static_cast<hipStream_t>(cfg->stream_side);
-  c->fill_kernel = (cfg->flags & QSAC_FLAG_FILL_KERNEL) != 0;
-  c->overlap = cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main && !(cfg->flags & QSAC_FLAG_SERIAL);
-  c->profile = (cfg->flags & QSAC_FLAG_PROFILE) != 0;
-  if (c->profile) c->overlap = false;  // stage times are taken on one stream
-  c->k_bound = 0;
-  c->steps = 0;
-  c->broken = false;
-  c->seen_K_src = c->seen_V_src = nullptr;
-  c->K_src_host = c->V_src_host = false;
-  c->ev_sel = c->ev_fill = nullptr;
-  for (auto& e : c->prof) e = nullptr;
+  fill_ctx(c, cfg, L);
   if (dry) {
     *out = c;
     return QSAC_OK;
