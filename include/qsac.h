@@ -242,6 +242,25 @@ int qsac_graph_free(qsac_graph *graph);
 int qsac_last_hip_error(void);
 
 /*
+ * qsac_step() for callers that cannot allocate device memory (code under graph capture, serving loops and
+ * harnesses in which hipMalloc is forbidden) and therefore cannot bring a workspace: the library's state and
+ * scratch of ONE layer live in a QSAC_STATIC_SCRATCH_BYTES array inside the library's device image, of which
+ * every GPU the library runs on holds a copy until the process ends.  The call allocates nothing on the
+ * device or the host, creates no events and copies nothing synchronously.
+ *   cfg    as for qsac_init(); workspace / workspace_bytes are ignored, stream_side must be NULL, flags may
+ *          hold QSAC_FLAG_SCORE_VALU and QSAC_FLAG_FILL_KERNEL only.  QSAC_EWORKSPACE if
+ *          qsac_workspace_bytes(cfg) exceeds QSAC_STATIC_SCRATCH_BYTES.
+ *   args   as for qsac_step(); inputs and outputs stay caller-owned.
+ *   reset  non-zero: first mark every head's cache invalid and zero the counters (as qsac_init / qsac_reset
+ *          do).  Required on the first call on a GPU and whenever cfg differs from the previous call's
+ *          (QSAC_ESTATE otherwise); the array keeps the previous call's contents.
+ * The array is per GPU (the current device of the calling thread), and every call on that GPU shares it:
+ * calls that overlap on one GPU, from several threads or streams, race.
+ */
+enum { QSAC_STATIC_SCRATCH_BYTES = 32 << 20 };
+int qsac_step_static(const qsac_config *cfg, const qsac_step_args *args, int reset);
+
+/*
  * Stage timing, for contexts created with QSAC_FLAG_PROFILE.  The stages of a step, in launch
  * order, are: 0 "gate" (qsac_gate_kernel), 1 "score" (qsac_score_mfma_kernel or
  * qsac_score_valu_kernel), 2 "select" (qsac_select_small_kernel for N <= 65536, else

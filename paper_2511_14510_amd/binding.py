@@ -24,7 +24,8 @@ QSAC_MAX_GROUP, QSAC_MAX_KV_HEADS, QSAC_HEAD_DIM = 8, 64, 128
 EXPORTS = ("qsac_workspace_bytes", "qsac_workspace_layout", "qsac_init", "qsac_reset", "qsac_step",
            "qsac_get_stats", "qsac_free", "qsac_strerror", "qsac_last_hip_error", "qsac_num_stages",
            "qsac_stage_name", "qsac_get_stage_ms", "qsac_adaptive_thresholds", "qsac_reuse_difficulty",
-           "qsac_graph_capture", "qsac_graph_launch", "qsac_graph_free")
+           "qsac_graph_capture", "qsac_graph_launch", "qsac_graph_free", "qsac_step_static")
+QSAC_STATIC_SCRATCH_BYTES = 32 << 20
 CALIB_EXPORTS = ("qsac_calibration_copy", "qsac_calibration_read")
 
 
@@ -92,6 +93,7 @@ def load():
         L.qsac_graph_capture.argtypes = [C.c_void_p, C.POINTER(qsac_step_args), C.POINTER(C.c_void_p)]
         L.qsac_graph_launch.argtypes = [C.c_void_p]
         L.qsac_graph_free.argtypes = [C.c_void_p]
+        L.qsac_step_static.argtypes = [C.POINTER(qsac_config), C.POINTER(qsac_step_args), C.c_int]
         fp = C.POINTER(C.c_float)
         L.qsac_adaptive_thresholds.argtypes = [fp, C.c_int32, C.c_float, C.c_float, fp]
         L.qsac_reuse_difficulty.argtypes = [fp, fp, C.c_int32, C.c_float, fp]
@@ -230,6 +232,12 @@ def qsac_reuse_difficulty(tau, avg_sim, eps: float) -> list:
     if rc:
         raise QsacError(rc, "qsac_reuse_difficulty")
     return list(out)
+
+
+def qsac_step_static(cfg: qsac_config, args: qsac_step_args, reset: bool) -> None:
+    rc = load().qsac_step_static(C.byref(cfg), C.byref(args), int(bool(reset)))
+    if rc:
+        raise QsacError(rc, "qsac_step_static")
 
 
 def qsac_free(ctx) -> None:

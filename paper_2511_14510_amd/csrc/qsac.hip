@@ -135,6 +135,11 @@ struct qsac_graph {
   int k;
 };
 
+// State and scratch of qsac_step_static(): one copy per GPU inside the library's device image.  In host code
+// this name is only a handle for hipGetSymbolAddress(); the device address it resolves to (per device) is what
+// kernels and the workspace layout use.
+static __device__ __align__(256) unsigned char scratch[QSAC_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 #define HIP_TRY(expr)                 \
@@ -710,6 +715,82 @@ int qsac_graph_free(qsac_graph* g) {
   (void)hipGraphExecDestroy(g->exec);
   g->magic = 0;
   delete g;
+  return QSAC_OK;
+}
+
+namespace {
+
+constexpr int kMaxStaticDevices = 64;
+struct StaticSlot {
+  bool ready;     // the device address of `scratch` is known and the LDS limits are raised on this device
+  bool bound;     // a reset has bound a configuration
+  void* ptr;      // device address of this GPU's copy of `scratch`
+  qsac_ctx ctx;   // the layer context that lives in it (host fields; no events, no second stream)
+};
+StaticSlot g_static[kMaxStaticDevices];
+
+bool same_shape(const qsac_config& a, const qsac_config& b) {
+  return a.batch == b.batch && a.n_q_heads == b.n_q_heads && a.n_kv_heads == b.n_kv_heads && a.head_dim == b.head_dim &&
+         a.n_ctx == b.n_ctx && a.k_max == b.k_max && a.dtype == b.dtype && a.flags == b.flags && a.n_sink == b.n_sink &&
+         a.n_recent == b.n_recent && a.append_capacity == b.append_capacity && a.stream_main == b.stream_main;
+}
+
+}  // namespace
+
+int qsac_step_static(const qsac_config* cfg, const qsac_step_args* a, int reset) {
+  if (!cfg || !a) return QSAC_ENULL;
+  int rc = check_config(cfg);
+  if (rc != QSAC_OK) return rc;
+  if (cfg->flags & ~(QSAC_FLAG_SCORE_VALU | QSAC_FLAG_FILL_KERNEL)) return QSAC_EINVAL;
+  if (cfg->stream_side) return QSAC_EINVAL;
+  qsac_ws_layout L;
+  make_layout(cfg, &L);
+  if (L.total > (size_t)QSAC_STATIC_SCRATCH_BYTES) return QSAC_EWORKSPACE;
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxStaticDevices) return QSAC_ERANGE;
+  StaticSlot& S = g_static[dev];
+  if (!S.ready) {
+    // once per device, with that device current: every GPU holds its own copy of the array at its own address
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255u)) return QSAC_EWORKSPACE;
+    rc = raise_lds_limits();
+    if (rc != QSAC_OK) return rc;
+    S.ptr = ptr;
+    S.ready = true;
+  }
+  if (reset) {
+    qsac_ctx fresh;
+    fill_ctx(&fresh, cfg, L);
+    fresh.cfg.workspace = S.ptr;
+    fresh.cfg.workspace_bytes = QSAC_STATIC_SCRATCH_BYTES;
+    rc = validate_step(&fresh, a);  // before anything is enqueued or the bound configuration changes
+    if (rc != QSAC_OK) return rc;
+    S.ctx = fresh;
+    S.bound = true;
+    // what must start at zero (validity flags, counters) is cleared by kernels on stream_main; everything else in
+    // the array is written before it is read
+    rc = set_importance(&S.ctx, cfg->q_head_importance);
+    if (rc == QSAC_OK) rc = clear_state(&S.ctx);
+    if (rc != QSAC_OK) {
+      S.bound = false;
+      return rc;
+    }
+  } else {
+    if (!S.bound || !same_shape(S.ctx.cfg, *cfg)) return QSAC_ESTATE;
+    rc = validate_step(&S.ctx, a);
+    if (rc != QSAC_OK) return rc;
+  }
+  qsac_ctx* c = &S.ctx;
+  note_fill_sources(c, a);
+  rc = enqueue_step(c, a);
+  if (rc != QSAC_OK) {
+    c->broken = true;  // only a call with reset clears this
+    return rc;
+  }
+  c->k_bound = a->k;
+  c->steps += 1;
   return QSAC_OK;
 }
 
