@@ -6,11 +6,19 @@ missing heads, top-k select, slot diff, miss fill, sparse attention).  Inputs ar
 (see paper_2511_14510_amd/workload.py) and resident in HBM (and, for the offload workloads,
 in pinned host memory) before the timed region starts.  Prints one JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--tau T]
+  python bench.py [--gpus 1] [--steps K] [--warmup W]          all five workloads; headline = the largest
+  python bench.py --workload NAME [--tau T] [--flags F] ...    one workload in detail (what the profiles run)
+
+With no --workload every workload of the benchmark is timed in one run: the headline fields (value,
+ms_per_step, config, roofline, cpu_baseline) are those of the largest one, low_sim_stress, whose step is bound
+by the PCIe fetch of the missing rows; the other four are summarised under "workloads".
 """
 import argparse
+import ctypes
+import glob
 import json
 import os
+import re
 import sys
 import time
 
@@ -19,20 +27,17 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-
-# HBM bytes the scoring kernel moves per missing pair, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script (profiles/qsac_step_kernels__llama3_8b_32k_all_miss__pmc_{fetch,write}_size.txt): per launch of 64 missing
-# pairs FETCH_SIZE = 262431.7 units of 2.000 KiB and WRITE_SIZE = 8242.8 units of 1.000 KiB (units calibrated
-# against the 256-MiB qsac_copy_kernel of the same runs).  bench.py cannot collect counters itself.
-PMC_SCORE_BYTES_PER_MISSING_PAIR = {"llama3_8b_32k": (262431.7 * 2.000 + 8242.8 * 1.000) * 1024 / 64}
+HEADLINE = "low_sim_stress"
+ORDER = ("tiny", "llama3_8b_32k", "qwen25_14b_128k_offload", "long_1m", "low_sim_stress")
+STAGES = ("gate", "score", "select", "fill", "attn", "combine")
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
-    ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--workload", default="llama3_8b_32k")
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default=None, help="time only this workload, in detail")
     ap.add_argument("--tau", type=float, default=None, help="override the workload's threshold")
     ap.add_argument("--flags", type=int, default=0, help="extra qsac_config.flags (e.g. 4 = ALU scoring)")
     ap.add_argument("--decode-buffers", action="store_true",
@@ -43,7 +48,7 @@ def parse():
     ap.add_argument("--side-stream", action="store_true",
                     help="give the library a second stream (attention of reused heads, or the fill kernel, runs on it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-profile", action="store_true", help="skip the stage-timing passes")
+    ap.add_argument("--no-profile", action="store_true", help="skip the stage-timing passes and the extra legs")
     ap.add_argument("--k-fill-from-hbm", action="store_true",
                     help="not the workload as specified: take the missing K rows from the HBM copy of K that scoring "
                          "reads (K_src = K_dev), so that only V rows cross PCIe")
@@ -52,22 +57,15 @@ def parse():
                          "launch's and of the all-miss scoring launch's size: what a launch of that size can reach")
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="launch this many plain 256 MiB copies first (qsac_copy_kernel), to scale profiler counters")
-    ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = sized to ~15 s)")
+    ap.add_argument("--cpu-seconds", type=float, default=0.0, help="oracle time budget (0 = 15 s headline, 4 s others)")
     return ap.parse_args()
 
 
-def make_queries(w, W, n_steps):
-    import torch
-    chain = W.chain_for(w)
-    qs = [W.round_to(chain.next(), w.dtype) for _ in range(n_steps)]
-    return torch.stack(qs)
-
-
-def run_steps(sess, q_dev, tau, k, lo, hi):
-    for t in range(lo, hi):
-        if sess.K_app is not None:
-            sess.set_appended(t + 1)   # the token generated at step t has joined the append-only buffer
-        sess.step(q_dev[t], tau, k)
+def r4(x):
+    """Four significant digits: keeps the line short."""
+    if x is None:
+        return None
+    return float(f"{x:.4g}")
 
 
 def h2d_peak_gbs(torch):
@@ -84,26 +82,398 @@ def h2d_peak_gbs(torch):
     return 3 * n / (time.perf_counter() - t0) / 1e9
 
 
+# ---- recorded profiler figures (bench.py cannot collect counters itself): read from the tracked summaries
+
+def recorded_counter(workload, kernel_substr):
+    """HBM bytes per launch of a kernel from the tracked rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries of this
+    script on `workload` (a workload name, or name + "_all_miss" for the run with tau = 2), scaled by what the
+    same counters read for the 256-MiB qsac_copy_kernel of the same runs.  Returns (bytes or None, source files)."""
+    total, files = 0.0, []
+    for counter in ("fetch_size", "write_size"):
+        path = os.path.join(ROOT, "profiles", f"qsac_step_kernels__{workload}__pmc_{counter}.txt")
+        if not os.path.exists(path):
+            return None, []
+        rows = {}
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 6 and f[1] in ("FETCH_SIZE", "WRITE_SIZE"):
+                rows[f[0]] = float(f[3])
+        copy = [v for name, v in rows.items() if "qsac_copy_kernel" in name]
+        kern = [v for name, v in rows.items() if kernel_substr in name]
+        if not copy or not kern:
+            return None, []
+        unit = (256 << 20) / copy[0]                 # bytes per counter unit
+        total += kern[0] * unit
+        files.append(os.path.relpath(path, ROOT))
+    return total, files
+
+
+def recorded_trace_us(workload, kernel_substr):
+    """Average duration of a kernel in the tracked rocprofv3 --kernel-trace summary of this script on `workload`."""
+    path = os.path.join(ROOT, "profiles", f"qsac_step_kernels__{workload}__kernel_trace.txt")
+    if not os.path.exists(path):
+        return None, None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 6 and kernel_substr in f[0] and re.fullmatch(r"\d+", f[1]):
+            return float(f[2]), os.path.relpath(path, ROOT)
+    return None, None
+
+
+class Bench:
+    def __init__(self, a):
+        import torch
+        from paper_2511_14510_amd import binding as Q
+        from paper_2511_14510_amd import workload as W
+        assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
+        Q.load()
+        self.a, self.torch, self.Q, self.W = a, torch, Q, W
+        self._h2d = None
+
+    def h2d(self):
+        if self._h2d is None:
+            self._h2d = h2d_peak_gbs(self.torch)
+            self.torch.cuda.empty_cache()
+        return self._h2d
+
+    # ------------------------------------------------------------------ one workload
+    def run(self, name, K_steps, W_steps, detail, cpu_seconds):
+        """Times one workload.  detail: 'headline' | 'single' (every leg) or 'brief' (what the summary needs)."""
+        a, torch, Q, W = self.a, self.torch, self.Q, self.W
+        w = W.CONFIGS[name]
+        if a.k_fill_from_hbm:
+            import dataclasses
+            w = dataclasses.replace(w, host_k=False)
+        tau = w.tau if (a.tau is None or detail == "brief") else a.tau
+        total = K_steps + W_steps
+        single = detail == "single"
+        want_cpu = cpu_seconds > 0
+
+        # ---- inputs, resident before any timing
+        K_dev, V_dev = W.make_kv(w.B, w.Hkv, w.N, w.D, w.dtype, w.seed, device="cuda:0")
+        K_host = V_host = None
+        if w.host_k or want_cpu:
+            K_host = torch.empty(K_dev.shape, dtype=K_dev.dtype, pin_memory=w.host_k).copy_(K_dev)
+        if w.host_v or want_cpu:
+            V_host = torch.empty(V_dev.shape, dtype=V_dev.dtype, pin_memory=w.host_v).copy_(V_dev)
+        K_src = K_host if w.host_k else K_dev
+        V_src = V_host if w.host_v else V_dev
+        chain = W.chain_for(w)
+        q_all = torch.stack([W.round_to(chain.next(), w.dtype) for _ in range(total)])
+        V_res = res_slot = None
+        hard, D = [], []
+        if single and a.resident:
+            # reuse difficulty D_i = tau_i - (s_hat_i - eps) from the adjacent-query cosines of the chain itself
+            # (the paper profiles s_hat offline on sample sequences); the hardest heads become resident
+            qf = q_all.double()
+            cos = (qf[1:] * qf[:-1]).sum(-1) / (qf[1:].norm(dim=-1) * qf[:-1].norm(dim=-1))     # [T-1,B,Hq]
+            cos = cos.reshape(total - 1, w.B, w.Hkv, w.G).clamp_min(1e-6)
+            s_hat = (w.G / (1.0 / cos).sum(-1)).mean(dim=(0, 1))                                 # Eq. (2), then mean
+            D = Q.qsac_reuse_difficulty([tau] * w.Hkv, s_hat.tolist(), 0.1)
+            hard = sorted(sorted(range(w.Hkv), key=lambda h: -D[h])[:a.resident])
+            res_slot = [-1] * w.Hkv
+            for i, h in enumerate(hard):
+                res_slot[h] = i
+            V_res = torch.stack([V_dev[:, h] for h in hard], dim=1).contiguous()
+        if w.host_v:
+            V_dev = None  # the offload workloads keep V on the host only (and in V_res for resident heads)
+        q_dev = q_all.cuda()
+        K_app = V_app = None
+        n_sink = n_recent = 0
+        if single and a.decode_buffers:
+            # the generated tokens' KV are synthetic too and resident beforehand; a step only raises the valid count
+            n_sink, n_recent = 4, 64
+            K_app, V_app = W.make_kv(w.B, w.Hkv, total, w.D, w.dtype, w.seed + 7, device="cuda:0")
+        torch.cuda.synchronize()
+        user_flags = a.flags if single else 0
+
+        def session(flags, side=False):
+            return Q.Session(w.B, w.Hq, w.Hkv, w.N, w.k, w.dtype, K_dev, K_src, V_src, flags=flags | user_flags,
+                             side_stream=side or (single and a.side_stream), V_res=V_res, res_slot=res_slot,
+                             n_sink=n_sink, n_recent=n_recent, K_app=K_app, V_app=V_app)
+
+        def run_steps(sess, tau_r, lo, hi):
+            for t in range(lo, hi):
+                if sess.K_app is not None:
+                    sess.set_appended(t + 1)   # the token generated at step t has joined the append-only buffer
+                sess.step(q_dev[t], tau_r, w.k)
+
+        def timed(flags=0, side=False, tau_r=None):
+            """(seconds for K steps after W warm-up steps, counter deltas over the K steps)."""
+            tau_r = tau if tau_r is None else tau_r
+            sess = session(flags, side)
+            run_steps(sess, tau_r, 0, W_steps)
+            sess.sync()
+            torch.cuda.synchronize()
+            s0 = sess.stats()
+            t0 = time.perf_counter()
+            run_steps(sess, tau_r, W_steps, total)
+            sess.sync()
+            torch.cuda.synchronize()
+            el = time.perf_counter() - t0
+            s1 = sess.stats()
+            sess.close()
+            return el, {key: s1[key] - s0[key] for key in s1}
+
+        # ---- the timed run: K steps after W warm-up steps, no events inside
+        elapsed, d = timed()
+        pairs = w.P * K_steps
+        fresh_rows = d["slot_hits"] + d["slot_misses"]
+        res = {
+            "steps_per_s": K_steps / elapsed, "ms_per_step": 1e3 * elapsed / K_steps,
+            "reuse_rate": d["reuse_heads"] / pairs,
+            "slot_hit_rate": d["slot_hits"] / fresh_rows if fresh_rows else None,
+            "guided_select_rate": d["guided_selects"] / d["miss_heads"] if d["miss_heads"] else None,
+            "rows_filled_per_step": d["slot_misses"] / K_steps,
+            "host_bytes_per_step": d["bytes_filled_host"] / K_steps,
+        }
+        res["_w"], res["_tau"] = w, tau
+        if single:
+            res["_cfg_extra"] = {}
+            if a.decode_buffers:
+                res["_cfg_extra"].update({"n_sink": n_sink, "n_recent": n_recent, "append_rows_at_end": total})
+            if a.resident:
+                res["_cfg_extra"].update({"resident_kv_heads": hard, "reuse_difficulty": [round(x, 4) for x in D]})
+
+        # ---- stage timing (HIP events on the stream the kernels run on), same steps
+        if not a.no_profile:
+            def profile(tau_p, n_warm, n_steps, extra=0):
+                ps = session(Q.QSAC_FLAG_PROFILE | extra)
+                run_steps(ps, tau_p, 0, n_warm)
+                ps.sync()
+                _, ms0, c0 = Q.qsac_get_stage_ms(ps.ctx)
+                st0 = ps.stats()
+                run_steps(ps, tau_p, n_warm, n_warm + n_steps)
+                ps.sync()
+                names, ms1, c1 = Q.qsac_get_stage_ms(ps.ctx)
+                st1 = ps.stats()
+                ps.close()
+                assert c1 - c0 == n_steps and tuple(names) == STAGES
+                us = dict(zip(names, [1e3 * (y - x) / n_steps for x, y in zip(ms0, ms1)]))
+                return us, {key: (st1[key] - st0[key]) / n_steps for key in st1}
+
+            def hbm(us, dd):
+                """Algorithmic bytes per launch over the event-timed duration of the two HBM-bound kernels."""
+                score_bytes = 256.0 * w.N * dd["miss_heads"]       # K bytes one scoring launch has to read
+                attn_bytes = 512.0 * w.k * w.P                      # slot bytes one attention launch has to read
+                return {"score_us": us["score"], "score_bytes": score_bytes,
+                        "score_GBps": score_bytes / us["score"] / 1e3 if score_bytes else None,
+                        "attn_us": us["attn"], "attn_bytes": attn_bytes, "attn_GBps": attn_bytes / us["attn"] / 1e3,
+                        "missing_pairs": dd["miss_heads"]}
+
+            us, dd = profile(tau, W_steps, K_steps)
+            res["stage_us"] = us
+            res["hbm"] = hbm(us, dd)
+            n_all = min(K_steps, 16)
+            us2, dd2 = profile(2.0, 2, n_all)          # every pair misses every step: each launch reads all of K
+            res["all_miss"] = {"stage_us": us2, **hbm(us2, dd2), "rows_filled": dd2["slot_misses"]}
+            if w.host_k or w.host_v:
+                peak = self.h2d()
+                # fill on read (the default): the host bytes a step fetches over the attention kernel's duration
+                res["pcie"] = {"peak_GBps": peak, "peak_kind": "hipMemcpyAsync pinned H2D of 1 GiB, measured in this run",
+                               "fill_on_read_GBps": dd["bytes_filled_host"] / us["attn"] / 1e3,
+                               "fill_on_read_all_miss_GBps": dd2["bytes_filled_host"] / us2["attn"] / 1e3}
+                if detail != "brief" or name == "qwen25_14b_128k_offload":
+                    # the fill as a kernel of its own, so that the rate of the GPU-issued row fetches alone shows
+                    uf, df = profile(tau, W_steps, K_steps, extra=Q.QSAC_FLAG_FILL_KERNEL)
+                    res["pcie"]["fill_kernel_GBps"] = df["bytes_filled_host"] / uf["fill"] / 1e3
+                    res["pcie"]["fill_kernel_us"] = uf["fill"]
+                    # overlap efficiency of the side stream: (serial - overlapped) / fill time
+                    t_ser, _ = timed(Q.QSAC_FLAG_FILL_KERNEL, side=False)
+                    t_ovl, _ = timed(Q.QSAC_FLAG_FILL_KERNEL, side=True)
+                    res["overlap"] = {"serial_us": 1e6 * t_ser / K_steps, "side_stream_us": 1e6 * t_ovl / K_steps,
+                                      "fill_us": uf["fill"],
+                                      "efficiency": (t_ser - t_ovl) / K_steps * 1e6 / uf["fill"] if uf["fill"] else None}
+            if (detail != "brief" or name in ("tiny", "llama3_8b_32k")) and not (single and (a.decode_buffers or a.resident)):
+                res["graph"] = self.graph_leg(session, q_dev, tau, w, K_steps, W_steps)
+
+        # ---- read-only launches of the sizes of the two HBM-bound kernels (a yardstick, not part of the step)
+        if single and a.calibration_reads:
+            pool = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+            sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+            res["read_only_launch"] = {}
+            for tag, nbytes in (("attn", 512 * w.k * w.P), ("score_all_miss", 256 * w.N * w.P)):
+                nbytes = min(nbytes, 512 << 20) // 16 * 16
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                us_l = []
+                for r in range(a.calibration_reads + 2):
+                    off = (r * nbytes) % ((1 << 30) - nbytes + 256) // 256 * 256     # rotate: nothing stays in a cache
+                    ev[0].record()
+                    Q.qsac_calibration_read(pool.data_ptr() + off, nbytes, sink.data_ptr())   # null stream, as the events
+                    ev[1].record()
+                    ev[1].synchronize()
+                    if r >= 2:
+                        us_l.append(1e3 * ev[0].elapsed_time(ev[1]))
+                res["read_only_launch"][tag] = {"bytes": nbytes, "us_by_events": sum(us_l) / len(us_l),
+                                                "GBps_by_events": nbytes / (sum(us_l) / len(us_l) * 1e-6) / 1e9}
+            del pool
+
+        # ---- the oracle on the host cores of this box, a bounded sample of the same workload
+        if want_cpu:
+            res["cpu_baseline"] = self.cpu_leg(w, tau, K_host, V_host, q_all, cpu_seconds)
+        del K_dev, V_dev, K_host, V_host, K_src, V_src, q_dev, V_res, K_app, V_app
+        torch.cuda.empty_cache()
+        return res
+
+    # ------------------------------------------------------------------ eager launches against graph replay
+    def graph_leg(self, session, q_dev, tau, w, K_steps, W_steps):
+        """The same steps launched kernel by kernel and replayed from one captured graph (Section 2.3 of the
+        paper: launch overhead of short steps).  Both sides copy the step's query into the fixed buffer the
+        graph is bound to, so the difference is the launch mechanism alone."""
+        torch, Q = self.torch, self.Q
+        total = K_steps + W_steps
+        out = {}
+        for mode in ("eager", "replay"):
+            sess = session(0)
+            q_buf = torch.zeros_like(q_dev[0])
+            table = sess.dev_params_table([tau] * 1, [0])
+            dp = table[0].clone()
+            torch.cuda.synchronize()
+            graph = Q.qsac_graph_capture(sess.ctx, sess.step_args(q_buf, None, w.k, dev_params=dp)) if mode == "replay" else None
+            args = sess.step_args(q_buf, tau, w.k)
+
+            def go(lo, hi):
+                for t in range(lo, hi):
+                    sess.copy_on_main(q_buf, q_dev[t])
+                    if graph is not None:
+                        Q.qsac_graph_launch(graph)
+                    else:
+                        Q.qsac_step(sess.ctx, args)
+            go(0, W_steps)
+            sess.sync()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            go(W_steps, total)
+            sess.sync()
+            torch.cuda.synchronize()
+            out[mode + "_us"] = 1e6 * (time.perf_counter() - t0) / K_steps
+            if graph is not None:
+                Q.qsac_graph_free(graph)
+            sess.close()
+        return out
+
+    # ------------------------------------------------------------------ the oracle, timed
+    def cpu_leg(self, w, tau, K_host, V_host, q_all, seconds):
+        import numpy as np
+        import oracle
+        W = self.W
+        cores = oracle.num_threads()
+        Kb, Vb = W.bits(K_host), W.bits(V_host)
+        qb = W.bits(q_all)
+        n_pairs = min(w.P, cores)                       # one pair per thread; pairs are independent
+        mask = np.zeros(w.P, np.uint8)
+        mask[np.linspace(0, w.P - 1, n_pairs).round().astype(int)] = 1     # spread over batch and heads
+        n_pairs = int(mask.sum())
+        st = oracle.State.empty(w.B, w.Hq, w.Hkv, w.D, w.k)
+        code = W.DTYPE_CODES[w.dtype]
+        t0 = time.perf_counter()
+        oracle.step(st, qb[0], Kb, Kb, Vb, tau, w.k, code, pair_mask=mask)      # first step: every pair misses
+        first = time.perf_counter() - t0
+        n_cpu = max(2, min(len(qb) - 1, int(seconds / max(first * 0.6, 1e-3))))
+        t0 = time.perf_counter()
+        for t in range(1, 1 + n_cpu):
+            oracle.step(st, qb[t], Kb, Kb, Vb, tau, w.k, code, pair_mask=mask)
+        cpu_t = time.perf_counter() - t0
+        scale = n_pairs / w.P                            # linear in the number of pairs
+        return {"value": n_cpu / cpu_t * scale, "unit": "steps/s", "cores": cores, "kind": "oracle",
+                "sample": f"steps 2..{n_cpu + 1} of the same query chain on {n_pairs} of the {w.P} pairs (OpenMP over "
+                          f"pairs, rate scaled by {n_pairs}/{w.P}), after an untimed all-miss first step ({first:.2f} s)"}
+
+
+def config_of(res, Q, a):
+    w, tau = res["_w"], res["_tau"]
+    cfg = {"workload": w.name, "batch": w.B, "n_q_heads": w.Hq, "n_kv_heads": w.Hkv, "head_dim": w.D,
+           "n_ctx": w.N, "k": w.k, "tau": tau,
+           "rho": ("one per KV head, quantiles of U[%g, %g]" % w.rho_range) if w.rho_range else w.rho,
+           "K_fill_source": "pinned host" if w.host_k else "HBM", "V_fill_source": "pinned host" if w.host_v else "HBM",
+           "fill": "folded into attention loads"}
+    if a.workload:
+        cfg["scoring"] = "alu" if (a.flags & Q.QSAC_FLAG_SCORE_VALU) else "mfma"
+        if a.flags & Q.QSAC_FLAG_FILL_KERNEL:
+            cfg["fill"] = "own kernel"
+        if a.side_stream:
+            cfg["side_stream"] = "fill kernel" if (a.flags & Q.QSAC_FLAG_FILL_KERNEL) else "attention of reused heads"
+        cfg.update(res.get("_cfg_extra", {}))
+    return cfg
+
+
+def rooflines(res):
+    """The roofline objects of a workload: the dominant kernel's, and the HBM-bound scoring kernel's beside it."""
+    w = res["_w"]
+    h = res["hbm"]
+    out = {}
+    traffic, files = recorded_counter(w.name + "_all_miss", "qsac_score")
+    trace_us, trace_file = recorded_trace_us(w.name + "_all_miss", "qsac_score")
+    score = {"bound": "hbm", "kernel": "qsac_score_mfma_kernel", "achieved": r4(h["score_GBps"]), "peak": HBM_PEAK_GBS,
+             "unit": "GB/s", "frac": r4(h["score_GBps"] / HBM_PEAK_GBS) if h["score_GBps"] else None,
+             "bytes_per_launch": r4(h["score_bytes"]), "us_per_launch": r4(h["score_us"]), "timed_by": "HIP events",
+             "missing_pairs_per_launch": r4(h["missing_pairs"]),
+             "all_miss_frac": r4(res["all_miss"]["score_GBps"] / HBM_PEAK_GBS),
+             # recorded with rocprofv3 on the same command, not measured in this run
+             "traffic": None, "traffic_source": None, "frac_by_recorded_trace": None, "trace_source": trace_file}
+    if traffic is not None:
+        # the summaries hold an all-miss run (P missing pairs per launch): scale to this run's missing pairs
+        score["traffic"] = r4(traffic * h["missing_pairs"] / w.P)
+        score["traffic_source"] = files
+    if trace_us:
+        score["frac_by_recorded_trace"] = r4(256.0 * w.N * w.P / trace_us / 1e3 / HBM_PEAK_GBS)
+    attn = {"bound": "hbm", "kernel": "qsac_attn_kernel", "achieved": r4(h["attn_GBps"]), "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": r4(h["attn_GBps"] / HBM_PEAK_GBS), "bytes_per_launch": r4(h["attn_bytes"]),
+            "us_per_launch": r4(h["attn_us"]), "timed_by": "HIP events"}
+    out["score"], out["attn"] = score, attn
+    if "pcie" in res:
+        p = res["pcie"]
+        out["pcie"] = {"bound": "pcie", "kernel": "qsac_attn_kernel (missing rows fetched from pinned host memory on read)",
+                       "achieved": r4(p["fill_on_read_GBps"]), "peak": r4(p["peak_GBps"]), "unit": "GB/s",
+                       "frac": r4(p["fill_on_read_GBps"] / p["peak_GBps"]),
+                       "bytes_per_launch": r4(res["host_bytes_per_step"]), "us_per_launch": r4(h["attn_us"]),
+                       "timed_by": "HIP events", "peak_kind": p["peak_kind"],
+                       "all_miss_frac": r4(p["fill_on_read_all_miss_GBps"] / p["peak_GBps"])}
+        # HBM bytes of the same kernel as recorded with rocprofv3 on this workload at its own threshold
+        traffic, files = recorded_counter(w.name, "qsac_attn")
+        out["pcie"]["traffic"] = r4(traffic) if traffic is not None else None
+        out["pcie"]["traffic_source"] = files or None
+        if "fill_kernel_GBps" in p:
+            out["pcie"]["fill_kernel_frac"] = r4(p["fill_kernel_GBps"] / p["peak_GBps"])
+    return out
+
+
+def brief(res):
+    """The summary of a workload that is not the headline."""
+    o = {"steps_per_s": r4(res["steps_per_s"]), "ms_per_step": r4(res["ms_per_step"]), "reuse_rate": r4(res["reuse_rate"]),
+         "tau": res["_tau"]}
+    if "hbm" in res:
+        h, am = res["hbm"], res["all_miss"]
+        o["score_hbm_frac"] = r4(h["score_GBps"] / HBM_PEAK_GBS) if h["score_GBps"] else None
+        o["score_hbm_frac_all_miss"] = r4(am["score_GBps"] / HBM_PEAK_GBS)
+        o["attn_hbm_frac"] = r4(h["attn_GBps"] / HBM_PEAK_GBS)
+        o["stage_us"] = {s: r4(res["stage_us"][s]) for s in STAGES}
+    if "pcie" in res:
+        p = res["pcie"]
+        o["fill"] = {"GBps": r4(p["fill_on_read_GBps"]), "h2d_GBps": r4(p["peak_GBps"]),
+                     "frac": r4(p["fill_on_read_GBps"] / p["peak_GBps"]),
+                     "all_miss_frac": r4(p["fill_on_read_all_miss_GBps"] / p["peak_GBps"])}
+        if "fill_kernel_GBps" in p:
+            o["fill"]["fill_kernel_frac"] = r4(p["fill_kernel_GBps"] / p["peak_GBps"])
+    if "overlap" in res:
+        o["overlap"] = {k: r4(v) for k, v in res["overlap"].items()}
+    if "graph" in res:
+        o["graph"] = {k: r4(v) for k, v in res["graph"].items()}
+    if "cpu_baseline" in res:
+        c = res["cpu_baseline"]
+        o["oracle"] = {"steps_per_s": r4(c["value"]), "cores": c["cores"]}
+    return o
+
+
 def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (the QSAC step has no inter-GPU part); use --gpus 1",
               file=sys.stderr)
         return 2
-    import numpy as np
-    import torch
-    from paper_2511_14510_amd import binding as Q
-    from paper_2511_14510_amd import workload as W
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
-    Q.load()
-    w = W.CONFIGS[a.workload]
-    if a.k_fill_from_hbm:
-        import dataclasses
-        w = dataclasses.replace(w, host_k=False)
-    tau = w.tau if a.tau is None else a.tau
+    B = Bench(a)
+    Q, torch = B.Q, B.torch
     K_steps, W_steps = a.steps, a.warmup
-    total = K_steps + W_steps
 
     if a.calibration_copies:
         n = 256 << 20
@@ -115,191 +485,49 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- inputs, resident before any timing
-    K_dev, V_dev = W.make_kv(w.B, w.Hkv, w.N, w.D, w.dtype, w.seed, device="cuda:0")
-    K_host = V_host = None
-    if w.host_k or w.host_v or not a.no_cpu_baseline:
-        K_host = torch.empty(K_dev.shape, dtype=K_dev.dtype, pin_memory=True).copy_(K_dev)
-        V_host = torch.empty(V_dev.shape, dtype=V_dev.dtype, pin_memory=True).copy_(V_dev)
-    K_src = K_host if w.host_k else K_dev
-    V_src = V_host if w.host_v else V_dev
-    q_all = make_queries(w, W, total)
-    V_res = res_slot = None
-    if a.resident:
-        # reuse difficulty D_i = tau_i - (s_hat_i - eps) from the adjacent-query cosines of the chain itself
-        # (the paper profiles s_hat offline on sample sequences); the hardest heads become resident
-        qf = q_all.double()
-        cos = (qf[1:] * qf[:-1]).sum(-1) / (qf[1:].norm(dim=-1) * qf[:-1].norm(dim=-1))     # [T-1,B,Hq]
-        cos = cos.reshape(total - 1, w.B, w.Hkv, w.G).clamp_min(1e-6)
-        s_hat = (w.G / (1.0 / cos).sum(-1)).mean(dim=(0, 1))                                 # Eq. (2), then mean
-        D = Q.qsac_reuse_difficulty([tau] * w.Hkv, s_hat.tolist(), 0.1)
-        hard = sorted(range(w.Hkv), key=lambda h: -D[h])[:a.resident]
-        res_slot = [-1] * w.Hkv
-        for i, h in enumerate(sorted(hard)):
-            res_slot[h] = i
-        V_res = torch.stack([V_dev[:, h] for h in sorted(hard)], dim=1).contiguous()
-    if w.host_v:
-        V_dev = None  # the offload workloads keep V on the host only (and in V_res for resident heads)
-    q_dev = q_all.cuda()
-    K_app = V_app = None
-    n_sink = n_recent = 0
-    if a.decode_buffers:
-        # the generated tokens' KV are synthetic too and resident beforehand; a step only raises the valid count
-        n_sink, n_recent = 4, 64
-        K_app, V_app = W.make_kv(w.B, w.Hkv, total, w.D, w.dtype, w.seed + 7, device="cuda:0")
-    torch.cuda.synchronize()
+    names = [a.workload] if a.workload else list(ORDER)
+    head_name = a.workload or HEADLINE
+    results = {}
+    for name in names:
+        is_head = name == head_name
+        detail = "single" if a.workload else ("headline" if is_head else "brief")
+        cpu_s = 0.0 if a.no_cpu_baseline else (a.cpu_seconds or (15.0 if is_head else 4.0))
+        t0 = time.perf_counter()
+        results[name] = B.run(name, K_steps, W_steps, detail, cpu_s)
+        print(f"bench.py: {name} done in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
 
-    def session(flags):
-        return Q.Session(w.B, w.Hq, w.Hkv, w.N, w.k, w.dtype, K_dev, K_src, V_src, flags=flags | a.flags,
-                         side_stream=bool(a.side_stream), V_res=V_res, res_slot=res_slot, n_sink=n_sink,
-                         n_recent=n_recent, K_app=K_app, V_app=V_app)
-
-    # ---- timed run: K steps after W warmup steps, overlapped fill, no events inside
-    sess = session(0)
-    run_steps(sess, q_dev, tau, w.k, 0, W_steps)
-    sess.sync()
-    torch.cuda.synchronize()
-    s0 = sess.stats()
-    t0 = time.perf_counter()
-    run_steps(sess, q_dev, tau, w.k, W_steps, total)
-    sess.sync()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    s1 = sess.stats()
-    sess.close()
-    d = {key: s1[key] - s0[key] for key in s1}
-    pairs = w.P * K_steps
-    reuse_rate = d["reuse_heads"] / pairs
-    fresh_rows = d["slot_hits"] + d["slot_misses"]
-    slot_hit_rate = d["slot_hits"] / fresh_rows if fresh_rows else None
-
-    result = {
-        "metric": "QSAC decode steps/s per layer", "value": K_steps / elapsed, "unit": "steps/s",
-        "n_gpus": 1, "steps": K_steps, "warmup": W_steps, "ms_per_step": 1e3 * elapsed / K_steps,
+    head = results[head_name]
+    w = head["_w"]
+    line = {
+        "metric": "QSAC decode steps/s per layer", "value": head["steps_per_s"], "unit": "steps/s",
+        "n_gpus": 1, "steps": K_steps, "warmup": W_steps, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "batch": w.B, "n_q_heads": w.Hq, "n_kv_heads": w.Hkv, "head_dim": w.D,
-                   "n_ctx": w.N, "k": w.k, "tau": tau, "rho": list(w.rho_range) if w.rho_range else w.rho,
-                   "K_fill_source": "pinned host" if w.host_k else "HBM",
-                   "V_fill_source": "pinned host" if w.host_v else "HBM",
-                   "scoring": "alu" if (a.flags & Q.QSAC_FLAG_SCORE_VALU) else "mfma",
-                   "fill": "own kernel on a side stream" if (a.flags & Q.QSAC_FLAG_FILL_KERNEL) else "folded into attention loads",
-                   "side_stream": (("fill kernel" if (a.flags & Q.QSAC_FLAG_FILL_KERNEL) else "attention of reused heads")
-                                   if a.side_stream else None)},
-        "reuse_rate": reuse_rate, "slot_hit_rate": slot_hit_rate,
-        "guided_select_rate": d["guided_selects"] / d["miss_heads"] if d["miss_heads"] else None,
-        "rows_filled_per_step": d["slot_misses"] / K_steps,
-        "rows_filled_from_host_per_step": ((d["slot_misses"] - d["resident_rows"]) / K_steps
-                                           if (w.host_k or w.host_v) else 0.0),
+        "config": config_of(head, Q, a),
+        "reuse_rate": r4(head["reuse_rate"]), "slot_hit_rate": r4(head["slot_hit_rate"]),
+        "guided_select_rate": r4(head["guided_select_rate"]),
+        "rows_filled_per_step": r4(head["rows_filled_per_step"]), "host_bytes_per_step": r4(head["host_bytes_per_step"]),
     }
-    if a.decode_buffers:
-        result["config"].update({"n_sink": n_sink, "n_recent": n_recent, "append_rows_at_end": total})
-    if a.resident:
-        result["config"]["resident_kv_heads"] = sorted(hard)
-        result["config"]["reuse_difficulty"] = [round(x, 4) for x in D]
-
-    # ---- stage timing (HIP events on the stream the kernels run on), same steps, fill not overlapped
-    if not a.no_profile:
-        def profile(tau_p, n_warm, n_steps, extra=0):
-            ps = session(Q.QSAC_FLAG_PROFILE | extra)
-            run_steps(ps, q_dev, tau_p, w.k, 0, n_warm)
-            ps.sync()
-            _, ms0, c0 = Q.qsac_get_stage_ms(ps.ctx)
-            st0 = ps.stats()
-            run_steps(ps, q_dev, tau_p, w.k, n_warm, n_warm + n_steps)
-            ps.sync()
-            names, ms1, c1 = Q.qsac_get_stage_ms(ps.ctx)
-            st1 = ps.stats()
-            ps.close()
-            assert c1 - c0 == n_steps
-            us = [1e3 * (y - x) / n_steps for x, y in zip(ms0, ms1)]
-            return names, us, {key: st1[key] - st0[key] for key in st1}
-
-        def roof(us, dd, n_steps):
-            miss_per_launch = dd["miss_heads"] / n_steps
-            score_bytes = 256.0 * w.N * miss_per_launch          # K bytes one scoring launch has to read
-            attn_bytes = 512.0 * w.k * w.P                        # slot bytes one attention launch has to read
-            return {
-                "score": {"bound": "hbm", "achieved": score_bytes / (us[1] * 1e-6) / 1e9 if miss_per_launch else 0.0,
-                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "bytes_per_launch": score_bytes,
-                          "us_per_launch": us[1], "missing_pairs_per_launch": miss_per_launch},
-                "attn": {"bound": "hbm", "achieved": attn_bytes / (us[4] * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
-                         "unit": "GB/s", "bytes_per_launch": attn_bytes, "us_per_launch": us[4]},
-            }
-
-        names, us, dd = profile(tau, W_steps, K_steps)
-        r = roof(us, dd, K_steps)
-        sc = r["score"]
-        result["roofline"] = {"bound": "hbm", "kernel": names[1], "achieved": sc["achieved"], "peak": HBM_PEAK_GBS,
-                              "unit": "GB/s", "frac": sc["achieved"] / HBM_PEAK_GBS,
-                              "traffic": (PMC_SCORE_BYTES_PER_MISSING_PAIR[w.name] * sc["missing_pairs_per_launch"]
-                                          if w.name in PMC_SCORE_BYTES_PER_MISSING_PAIR and not a.flags else None),
-                              "bytes_per_launch": sc["bytes_per_launch"], "us_per_launch": sc["us_per_launch"],
-                              "missing_pairs_per_launch": sc["missing_pairs_per_launch"]}
-        result["stage_us"] = dict(zip(names, [round(x, 2) for x in us]))
-        result["attn_roofline"] = {**r["attn"], "frac": r["attn"]["achieved"] / HBM_PEAK_GBS}
-        # every pair misses every step: each scoring launch reads all of K
-        n_all = min(K_steps, 32)
-        names, us2, dd2 = profile(2.0, 2, n_all)
-        r2 = roof(us2, dd2, n_all)
-        result["all_miss"] = {"tau": 2.0, "steps": n_all, "stage_us": dict(zip(names, [round(x, 2) for x in us2])),
-                              "score_GBps": r2["score"]["achieved"], "score_frac": r2["score"]["achieved"] / HBM_PEAK_GBS,
-                              "attn_GBps": r2["attn"]["achieved"], "attn_frac": r2["attn"]["achieved"] / HBM_PEAK_GBS,
-                              "rows_filled_per_step": dd2["slot_misses"] / n_all}
-        if w.host_k or w.host_v:
-            # the miss fill as a kernel of its own (not folded into the attention loads), so that the PCIe
-            # rate of the GPU-issued row fetches can be read off its duration
-            peak = h2d_peak_gbs(torch)
-            per_row = 256 * (int(w.host_k) + int(w.host_v))
-            for tag, tau_f, nw, ns in (("fill", tau, W_steps, K_steps), ("fill_all_miss", 2.0, 2, n_all)):
-                _, uf, df = profile(tau_f, nw, ns, extra=Q.QSAC_FLAG_FILL_KERNEL)
-                by = per_row * df["slot_misses"] / ns
-                gbs = by / (uf[3] * 1e-6) / 1e9 if by else 0.0
-                result[tag] = {"bound": "pcie", "kernel": "qsac_fill_kernel", "bytes_per_launch": by,
-                               "us_per_launch": uf[3], "achieved": gbs, "peak": peak, "unit": "GB/s",
-                               "frac": gbs / peak, "peak_kind": "measured hipMemcpyAsync pinned H2D, 1 GiB"}
-
-    # ---- read-only launches of the sizes of the two HBM-bound kernels (a yardstick, not part of the step)
-    if a.calibration_reads:
-        pool = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
-        sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
-        result["read_only_launch"] = {}
-        for name, nbytes in (("attn", 512 * w.k * w.P), ("score_all_miss", 256 * w.N * w.P)):
-            nbytes = min(nbytes, 512 << 20) // 16 * 16
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            us = []
-            for r in range(a.calibration_reads + 2):
-                off = (r * nbytes) % ((1 << 30) - nbytes + 256) // 256 * 256     # rotate: nothing stays in a cache
-                ev[0].record()
-                Q.qsac_calibration_read(pool.data_ptr() + off, nbytes, sink.data_ptr())   # on the null stream, as the events
-                ev[1].record()
-                ev[1].synchronize()
-                if r >= 2:
-                    us.append(1e3 * ev[0].elapsed_time(ev[1]))
-            result["read_only_launch"][name] = {"bytes": nbytes, "us_by_events": sum(us) / len(us),
-                                                "GBps_by_events": nbytes / (sum(us) / len(us) * 1e-6) / 1e9}
-        del pool
-
-    # ---- the oracle on the host cores of this machine, a bounded sample of the same workload
-    if not a.no_cpu_baseline:
-        import oracle
-        Kb, Vb = W.bits(K_host), W.bits(V_host)
-        qb = W.bits(q_dev.cpu())
-        st = oracle.State.empty(w.B, w.Hq, w.Hkv, w.D, w.k)
-        code = W.DTYPE_CODES[w.dtype]
-        t0 = time.perf_counter()
-        oracle.step(st, qb[0], Kb, Kb, Vb, tau, w.k, code)      # first step: every pair misses
-        first = time.perf_counter() - t0
-        n_cpu = a.cpu_steps or max(2, min(K_steps + W_steps - 1, int(15.0 / max(first * 0.5, 1e-3))))
-        t0 = time.perf_counter()
-        for t in range(1, 1 + n_cpu):
-            oracle.step(st, qb[t], Kb, Kb, Vb, tau, w.k, code)
-        cpu_t = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": n_cpu / cpu_t, "unit": "steps/s", "cores": oracle.num_threads(),
-                                  "kind": "oracle",
-                                  "sample": f"steps 2..{n_cpu + 1} of the same query chain on the full batch "
-                                            f"({w.P} pairs, OpenMP over pairs), after an untimed all-miss first step "
-                                            f"({first:.2f} s)"}
-    print(json.dumps(result))
+    if "hbm" in head:
+        rf = rooflines(head)
+        # dominant kernel: the attention kernel fetching the missing rows over PCIe where the workload offloads,
+        # the scoring pass otherwise
+        line["roofline"] = rf["pcie"] if "pcie" in rf else rf["score"]
+        line["score_roofline"], line["attn_roofline"] = rf["score"], rf["attn"]
+        line["stage_us"] = {s: r4(head["stage_us"][s]) for s in STAGES}
+        line["all_miss"] = {"stage_us": {s: r4(head["all_miss"]["stage_us"][s]) for s in STAGES},
+                            "score_frac": r4(head["all_miss"]["score_GBps"] / HBM_PEAK_GBS),
+                            "attn_frac": r4(head["all_miss"]["attn_GBps"] / HBM_PEAK_GBS)}
+        for key in ("overlap", "graph"):
+            if key in head:
+                line[key] = {k: r4(v) for k, v in head[key].items()}
+    if "read_only_launch" in head:
+        line["read_only_launch"] = head["read_only_launch"]
+    if "cpu_baseline" in head:
+        line["cpu_baseline"] = head["cpu_baseline"]
+        line["cpu_baseline"]["value"] = r4(line["cpu_baseline"]["value"])
+    if not a.workload:
+        line["workloads"] = {n: brief(results[n]) for n in names if n != head_name}
+    print(json.dumps(line, separators=(",", ":")))
     return 0
 
 

@@ -265,7 +265,7 @@ int qsac_step_static(const qsac_config *cfg, const qsac_step_args *args, int res
  * order, are: 0 "gate" (qsac_gate_kernel), 1 "score" (qsac_score_mfma_kernel or
  * qsac_score_valu_kernel), 2 "select" (qsac_select_small_kernel for N <= 65536, else
  * qsac_refine_kernel<1>, <2>, qsac_mark_kernel, qsac_diff_kernel), 3 "fill" (qsac_fill_kernel),
- * 4 "attn" (qsac_attn_kernel, qsac_combine_kernel).  qsac_get_stage_ms() waits for the last profiled step and writes
+ * 4 "attn" (qsac_attn_kernel), 5 "combine" (qsac_combine_kernel).  qsac_get_stage_ms() waits for the last profiled step and writes
  * the summed duration of each stage in milliseconds to ms_sum[qsac_num_stages()] and the number
  * of steps summed to *n_steps.  A duration is the time between the events recorded on
  * stream_main before the stage's first kernel and before the next stage's.  qsac_stage_name(i)

@@ -18,8 +18,8 @@ namespace {
 
 constexpr uint32_t kMagic = 0x51534143u;       // "QSAC"
 constexpr uint32_t kGraphMagic = 0x51534147u;  // "QSAG"
-constexpr int kStages = 5;
-const char* const kStageNames[kStages] = {"gate", "score", "select", "fill", "attn"};
+constexpr int kStages = 6;
+const char* const kStageNames[kStages] = {"gate", "score", "select", "fill", "attn", "combine"};
 
 thread_local int g_last_hip = 0;
 
@@ -556,8 +556,9 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
     if (c->fill_kernel) fill_on(sm);
     mark(4);
     attend(sm, 0);
-    combine();
     mark(5);
+    combine();
+    mark(6);
     c->prof_pending = c->profile;
   }
   HIP_TRY(hipGetLastError());

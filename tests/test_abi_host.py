@@ -170,8 +170,8 @@ def test_strerror_and_stage_names(lib):
         assert Q.qsac_strerror(code) != "unknown error"
     assert Q.qsac_strerror(-99) == "unknown error"
     n = lib.qsac_num_stages()
-    assert n == 5 and lib.qsac_stage_name(n) is None
-    assert [lib.qsac_stage_name(i) for i in range(n)] == [b"gate", b"score", b"select", b"fill", b"attn"]
+    assert n == 6 and lib.qsac_stage_name(n) is None
+    assert [lib.qsac_stage_name(i) for i in range(n)] == [b"gate", b"score", b"select", b"fill", b"attn", b"combine"]
 
 
 def test_binding_has_no_cpu_fallback():
