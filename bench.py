@@ -360,16 +360,30 @@ class Bench:
         cores = oracle.num_threads()
         Kb, Vb = W.bits(K_host), W.bits(V_host)
         qb = W.bits(q_all)
-        n_pairs = min(w.P, cores)                       # one pair per thread; pairs are independent
-        mask = np.zeros(w.P, np.uint8)
-        mask[np.linspace(0, w.P - 1, n_pairs).round().astype(int)] = 1     # spread over batch and heads
-        n_pairs = int(mask.sum())
-        st = oracle.State.empty(w.B, w.Hq, w.Hkv, w.D, w.k)
         code = W.DTYPE_CODES[w.dtype]
-        t0 = time.perf_counter()
-        oracle.step(st, qb[0], Kb, Kb, Vb, tau, w.k, code, pair_mask=mask)      # first step: every pair misses
-        first = time.perf_counter() - t0
-        n_cpu = max(2, min(len(qb) - 1, int(seconds / max(first * 0.6, 1e-3))))
+        n_steps_max = len(qb) - 1
+
+        def sample_mask(n_pairs):
+            mask = np.zeros(w.P, np.uint8)
+            mask[np.linspace(0, w.P - 1, n_pairs).round().astype(int)] = 1     # spread over batch and heads
+            return mask
+
+        def first_step(mask):
+            st = oracle.State.empty(w.B, w.Hq, w.Hkv, w.D, w.k)
+            t0 = time.perf_counter()
+            oracle.step(st, qb[0], Kb, Kb, Vb, tau, w.k, code, pair_mask=mask)      # first step: every pair misses
+            return st, time.perf_counter() - t0
+
+        # one pair per thread first (pairs are independent); if the query chain at hand would not fill the time
+        # budget with that many pairs, the sample grows in whole rounds of `cores` pairs
+        mask = sample_mask(min(w.P, cores))
+        st, first = first_step(mask)
+        rounds = int(seconds / max(first * 0.6 * n_steps_max, 1e-3))
+        if rounds >= 2 and w.P > cores:
+            mask = sample_mask(min(w.P, cores * rounds))
+            st, first = first_step(mask)
+        n_pairs = int(mask.sum())
+        n_cpu = max(2, min(n_steps_max, int(seconds / max(first * 0.6, 1e-3))))
         t0 = time.perf_counter()
         for t in range(1, 1 + n_cpu):
             oracle.step(st, qb[t], Kb, Kb, Vb, tau, w.k, code, pair_mask=mask)

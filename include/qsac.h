@@ -55,7 +55,8 @@ enum {
   QSAC_EWORKSPACE = -4, /* workspace missing, misaligned or too small           */
   QSAC_EHIP = -5,       /* a HIP runtime call failed (see qsac_last_hip_error)  */
   QSAC_ESTATE = -6,     /* bad handle, k changed without qsac_reset, or a step failed with QSAC_EHIP */
-  QSAC_EALIGN = -7      /* a tensor pointer is not 16-byte aligned              */
+  QSAC_EALIGN = -7,     /* a tensor pointer is not 16-byte aligned              */
+  QSAC_ETIMEOUT = -8    /* push mode: a polling kernel gave up waiting for the host transfer threads */
 };
 
 enum {
@@ -70,9 +71,22 @@ enum {
   QSAC_FLAG_SERIAL = 2,      /* run everything on stream_main even when stream_side is given              */
   QSAC_FLAG_SCORE_VALU = 4,  /* score with packed dot-product ALU ops instead of the MFMA tile           */
   QSAC_FLAG_PROFILE = 8,     /* bracket every stage with timing events (single stream; see qsac_get_stage_ms) */
-  QSAC_FLAG_FILL_KERNEL = 16 /* fill the missing rows with a kernel of its own (on stream_side if given, overlapped
+  QSAC_FLAG_FILL_KERNEL = 16,/* fill the missing rows with a kernel of its own (on stream_side if given, overlapped
                                 with the attention of the heads that reused) instead of folding the fetch into the
                                 attention kernel's row loads                                              */
+  QSAC_FLAG_PUSH_FILL = 32,  /* push-mode transfer, the paper's own scheme (Section 5.2 GPU-centric synchronization,
+                                Section 6.2 zero-copy transfer engine) as an alternative to the GPU pulling the rows:
+                                the GPU publishes the compacted miss lists and a request flag (Flag1) in pinned host
+                                memory, host transfer threads owned by the context copy the rows from the host K / V
+                                store straight into the cache slots through the device's host-visible memory window
+                                and set a completion flag (Flag2), and a polling kernel holds back the attention of
+                                the heads that missed until it sees Flag2.  Both fill sources must then be host
+                                memory and no head may be resident (QSAC_EINVAL otherwise).  The polling kernel's
+                                wait is bounded (qsac_config.push_wait_us): if the flag does not arrive in time the
+                                kernel records the fact and exits, the step's results are invalid, and the next call
+                                on the context returns QSAC_ETIMEOUT until qsac_reset                         */
+  QSAC_FLAG_PUSH_HOLD = 64   /* test aid for push mode: the transfer threads ignore every request, so every polling
+                                kernel runs into its bound                                                  */
 };
 
 typedef struct qsac_ctx qsac_ctx;
@@ -96,6 +110,9 @@ typedef struct {
   int32_t n_sink, n_recent;
   /* Rows per KV head of the append-only buffer (Sections 6.1, 6.2), 0 = none; see qsac_step_args.K_app. */
   int32_t append_capacity;
+  /* Push mode (QSAC_FLAG_PUSH_FILL) only: host transfer threads (0 = 4; at most 64) and the longest a polling
+     kernel waits for them, in microseconds (0 = 2 000 000). */
+  int32_t push_threads, push_wait_us;
 } qsac_config;
 
 /* Byte offsets of the library's arrays inside the workspace (for tests and tools that inspect them). */
@@ -118,6 +135,8 @@ typedef struct {
                                              threshold bins found so far by the grid-wide select (last miss)      */
   size_t chunk_cnt;  /* i32 [P][n_pad/8192][2] set bits per 8192-key chunk of bm_new and bm_eq (long contexts)    */
   size_t fetch_tok;  /* i32 [P][k_max]       per slot: token whose rows the slot still has to receive, or -1      */
+  size_t push;       /* u32 [4]              push mode: request sequence number, pairs published so far, polls
+                                             that gave up                                                         */
   size_t total;      /* bytes needed                                                                      */
   int64_t n_pad;     /* N rounded up to the select chunk                                                  */
   int32_t words;     /* 32-bit words per bitmap                                                           */

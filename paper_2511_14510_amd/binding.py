@@ -17,8 +17,9 @@ CALIB_LIB_PATH = os.path.join(HERE, "csrc", "libqsac_calib.so")
 
 QSAC_F16, QSAC_BF16 = 0, 1
 QSAC_OK, QSAC_EINVAL, QSAC_ENULL, QSAC_ERANGE = 0, -1, -2, -3
-QSAC_EWORKSPACE, QSAC_EHIP, QSAC_ESTATE, QSAC_EALIGN = -4, -5, -6, -7
+QSAC_EWORKSPACE, QSAC_EHIP, QSAC_ESTATE, QSAC_EALIGN, QSAC_ETIMEOUT = -4, -5, -6, -7, -8
 QSAC_FLAG_DRY_RUN, QSAC_FLAG_SERIAL, QSAC_FLAG_SCORE_VALU, QSAC_FLAG_PROFILE, QSAC_FLAG_FILL_KERNEL = 1, 2, 4, 8, 16
+QSAC_FLAG_PUSH_FILL, QSAC_FLAG_PUSH_HOLD = 32, 64
 QSAC_MAX_GROUP, QSAC_MAX_KV_HEADS, QSAC_HEAD_DIM = 8, 64, 128
 
 EXPORTS = ("qsac_workspace_bytes", "qsac_workspace_layout", "qsac_init", "qsac_reset", "qsac_step",
@@ -34,13 +35,15 @@ class qsac_config(C.Structure):
                 ("n_ctx", C.c_int64), ("k_max", C.c_int32), ("dtype", C.c_int32),
                 ("q_head_importance", C.POINTER(C.c_float)), ("stream_main", C.c_void_p),
                 ("stream_side", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
-                ("flags", C.c_int32), ("n_sink", C.c_int32), ("n_recent", C.c_int32), ("append_capacity", C.c_int32)]
+                ("flags", C.c_int32), ("n_sink", C.c_int32), ("n_recent", C.c_int32), ("append_capacity", C.c_int32),
+                ("push_threads", C.c_int32), ("push_wait_us", C.c_int32)]
 
 
 class qsac_ws_layout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
                 ("valid", "set_sorted", "keys", "hist", "bm_new", "bm_eq", "bm_old", "miss_count", "miss_slot",
-                 "miss_tok", "part_ml", "part_acc", "stats", "importance", "sel_r", "chunk_cnt", "fetch_tok", "total")] + \
+                 "miss_tok", "part_ml", "part_acc", "stats", "importance", "sel_r", "chunk_cnt", "fetch_tok", "push",
+                 "total")] + \
                [("n_pad", C.c_int64), ("words", C.c_int32), ("max_splits", C.c_int32)]
 
 
@@ -247,8 +250,9 @@ def qsac_free(ctx) -> None:
 
 
 def make_config(B, Hq, Hkv, N, k_max, dtype, flags=0, importance=None, n_sink=0, n_recent=0,
-                append_capacity=0) -> qsac_config:
+                append_capacity=0, push_threads=0, push_wait_us=0) -> qsac_config:
     cfg = qsac_config()
+    cfg.push_threads, cfg.push_wait_us = push_threads, push_wait_us
     cfg.n_sink, cfg.n_recent, cfg.append_capacity = n_sink, n_recent, append_capacity
     cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = B, Hq, Hkv, QSAC_HEAD_DIM
     cfg.n_ctx, cfg.k_max, cfg.dtype, cfg.flags = N, k_max, dtype, flags
@@ -267,7 +271,8 @@ class Session:
     """
 
     def __init__(self, B, Hq, Hkv, N, k_max, dtype: str, K_dev, K_src, V_src, flags=0, importance=None,
-                 side_stream=False, V_res=None, res_slot=None, n_sink=0, n_recent=0, K_app=None, V_app=None):
+                 side_stream=False, V_res=None, res_slot=None, n_sink=0, n_recent=0, K_app=None, V_app=None,
+                 push_threads=0, push_wait_us=0):
         """V_res [B,n_res,N,128] (device) and res_slot [Hkv] make the KV heads with res_slot >= 0 resident."""
         import torch
         from .workload import DTYPE_CODES, TORCH_DTYPES
@@ -293,7 +298,8 @@ class Session:
             cap = K_app.shape[2]
             for t in (K_app, V_app):
                 assert t.is_cuda and t.is_contiguous() and t.dtype == tdt and t.shape == (B, Hkv, cap, 128)
-        cfg = make_config(B, Hq, Hkv, N, k_max, DTYPE_CODES[dtype], flags, importance, n_sink, n_recent, cap)
+        cfg = make_config(B, Hq, Hkv, N, k_max, DTYPE_CODES[dtype], flags, importance, n_sink, n_recent, cap,
+                          push_threads, push_wait_us)
         nbytes = qsac_workspace_bytes(cfg)
         if nbytes == 0:
             raise QsacError(QSAC_EINVAL, "qsac_workspace_bytes")

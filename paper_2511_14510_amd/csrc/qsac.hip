@@ -5,10 +5,16 @@
 
 #include <hip/hip_runtime.h>
 
+#include <immintrin.h>
+#include <time.h>
+
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <thread>
+#include <vector>
 
 #include "qsac_kernels.hip.h"
 
@@ -38,7 +44,12 @@ int check_config(const qsac_config* c) {
   if ((int64_t)c->batch * c->n_kv_heads > 65535) return QSAC_ERANGE;  // grid.y
   if (c->append_capacity < 0 || c->append_capacity > (1 << 20)) return QSAC_ERANGE;
   if (c->n_sink < 0 || c->n_recent < 0 || (int64_t)c->n_sink + c->n_recent > c->k_max) return QSAC_ERANGE;
-  if (c->flags & ~(QSAC_FLAG_DRY_RUN | QSAC_FLAG_SERIAL | QSAC_FLAG_SCORE_VALU | QSAC_FLAG_PROFILE | QSAC_FLAG_FILL_KERNEL)) return QSAC_EINVAL;
+  if (c->flags & ~(QSAC_FLAG_DRY_RUN | QSAC_FLAG_SERIAL | QSAC_FLAG_SCORE_VALU | QSAC_FLAG_PROFILE | QSAC_FLAG_FILL_KERNEL |
+                   QSAC_FLAG_PUSH_FILL | QSAC_FLAG_PUSH_HOLD))
+    return QSAC_EINVAL;
+  if ((c->flags & QSAC_FLAG_PUSH_HOLD) && !(c->flags & QSAC_FLAG_PUSH_FILL)) return QSAC_EINVAL;
+  if ((c->flags & QSAC_FLAG_PUSH_FILL) && (c->flags & QSAC_FLAG_FILL_KERNEL)) return QSAC_EINVAL;  // one way to fill
+  if (c->push_threads < 0 || c->push_threads > 64 || c->push_wait_us < 0) return QSAC_ERANGE;
   if (c->q_head_importance)
     for (int i = 0; i < c->n_q_heads; ++i)
       if (!(c->q_head_importance[i] > 0.f) || !std::isfinite(c->q_head_importance[i])) return QSAC_EINVAL;
@@ -100,6 +111,7 @@ void make_layout(const qsac_config* c, qsac_ws_layout* L) {
   L->sel_r = take(P * kSelStride * 4);
   L->chunk_cnt = take(P * (n_pad / kSelChunk) * 2 * 4);
   L->fetch_tok = take(P * c->k_max * 4);
+  L->push = take(4 * 4);
   L->total = off;
   L->n_pad = (int64_t)n_pad;
   L->words = (int32_t)words;
@@ -107,6 +119,96 @@ void make_layout(const qsac_config* c, qsac_ws_layout* L) {
 }
 
 }  // namespace
+
+// ---- push-mode transfer engine (Section 6.2 of the paper): host threads that copy the rows of a request's miss
+// lists from the host K / V store straight into the cache slots, through the device memory window the host can
+// write, and then raise the completion flag.
+struct PushJob {
+  const char* K_src;
+  const char* V_src;
+  char* K_slots;
+  char* V_slots;
+  int64_t N;
+  int k_max, P;
+};
+
+struct PushEngine {
+  static constexpr uint32_t kRing = 1024;  // requests the host may be ahead of the device
+  uint32_t* box = nullptr;                 // mailbox in pinned host memory (layout: qsac_publish_kernel)
+  int T = 0;
+  bool hold = false;
+  std::vector<std::thread> threads;
+  std::atomic<bool> stop{false};
+  std::atomic<int> arrived{0};
+  uint32_t submitted = 0;  // sequence number of the last request whose job is in the ring (host thread of the caller)
+  PushJob ring[kRing];
+
+  void start(uint32_t seq_now) {
+    stop.store(false);
+    arrived.store(0);
+    submitted = seq_now;
+    for (int i = 0; i < T; ++i) threads.emplace_back([this, i, seq_now] { worker(i, seq_now); });
+  }
+  void halt() {
+    stop.store(true);
+    for (auto& t : threads) t.join();
+    threads.clear();
+  }
+  void worker(int id, uint32_t seen) {
+    int idle = 0;
+    while (!stop.load(std::memory_order_relaxed)) {
+      const uint32_t f1 = __atomic_load_n(box + qsac::kPushFlag1, __ATOMIC_ACQUIRE);
+      if (hold || f1 == seen) {
+        // spin while requests keep coming, doze once the device has been quiet for a while
+        if (++idle < 200000) {
+          _mm_pause();
+        } else {
+          timespec ts = {0, 50000};
+          nanosleep(&ts, nullptr);
+        }
+        continue;
+      }
+      idle = 0;
+      const uint32_t seq = seen + 1;
+      const PushJob J = ring[seq % kRing];
+      const int* count = reinterpret_cast<const int*>(box + qsac::kPushHeaderWords);
+      const int* slot = count + J.P;
+      const int* tok = slot + (size_t)J.P * J.k_max;
+      long total = 0;
+      for (int p = 0; p < J.P; ++p) total += count[p];
+      // thread `id` takes the rows [lo, hi) of all pairs' lists laid end to end
+      const long lo = total * id / T, hi = total * (id + 1) / T;
+      long base = 0;
+      const volatile uint32_t* last = nullptr;
+      for (int p = 0; p < J.P && base < hi; ++p) {
+        const long c = count[p];
+        if (base + c > lo) {
+          const long e0 = lo > base ? lo - base : 0, e1 = hi - base < c ? hi - base : c;
+          const int* sp = slot + (size_t)p * J.k_max;
+          const int* tp = tok + (size_t)p * J.k_max;
+          const char* Ks = J.K_src + (size_t)p * (size_t)J.N * 256;
+          const char* Vs = J.V_src + (size_t)p * (size_t)J.N * 256;
+          char* Kd = J.K_slots + (size_t)p * (size_t)J.k_max * 256;
+          char* Vd = J.V_slots + (size_t)p * (size_t)J.k_max * 256;
+          for (long e = e0; e < e1; ++e) {
+            std::memcpy(Kd + (size_t)sp[e] * 256, Ks + (size_t)tp[e] * 256, 256);
+            std::memcpy(Vd + (size_t)sp[e] * 256, Vs + (size_t)tp[e] * 256, 256);
+            last = reinterpret_cast<const volatile uint32_t*>(Vd + (size_t)sp[e] * 256);
+          }
+        }
+        base += c;
+      }
+      _mm_sfence();
+      // a read through the same window cannot overtake the writes before it: once it returns they are in device memory
+      if (last) (void)*last;
+      if (arrived.fetch_add(1, std::memory_order_acq_rel) == T - 1) {
+        arrived.store(0, std::memory_order_relaxed);
+        __atomic_store_n(box + qsac::kPushFlag2, seq, __ATOMIC_RELEASE);  // the paper's Flag2
+      }
+      seen = seq;
+    }
+  }
+};
 
 struct qsac_ctx {
   uint32_t magic;
@@ -123,6 +225,7 @@ struct qsac_ctx {
   uint64_t stage_calls;
   bool prof_pending;
   bool broken;  // a HIP call failed in the middle of a step: the caches may be half updated, only a reset clears this
+  PushEngine* push;  // push-mode transfer engine, nullptr otherwise
   // where the fill sources of the last step live (looked up when the pointers change)
   const void *seen_K_src, *seen_V_src;
   bool K_src_host, V_src_host;
@@ -133,6 +236,7 @@ struct qsac_graph {
   qsac_ctx* ctx;
   hipGraphExec_t exec;
   int k;
+  PushJob job;  // push mode: what the transfer threads need for a replay
 };
 
 // State and scratch of qsac_step_static(): one copy per GPU inside the library's device image.  In host code
@@ -279,7 +383,7 @@ AttnArgs attn_args(const qsac_ctx* c, const qsac_step_args* a, const int* fetch_
 template <int DT, int G>
 void launch_attn(const qsac_ctx* c, hipStream_t stream, const AttnArgs& A, const FillSrc& src) {
   dim3 grid((unsigned)A.n_splits, (unsigned)c->P);
-  if (c->fill_kernel)
+  if (c->fill_kernel || c->push)  // the rows are in their slots before the attention starts
     qsac_attn_kernel<DT, G, false><<<grid, 256, 0, stream>>>(A, src);
   else
     qsac_attn_kernel<DT, G, true><<<grid, 256, 0, stream>>>(A, src);
@@ -328,6 +432,7 @@ void fill_ctx(qsac_ctx* c, const qsac_config* cfg, const qsac_ws_layout& L) {
   c->seen_K_src = c->seen_V_src = nullptr;
   c->K_src_host = c->V_src_host = false;
   c->ev_sel = c->ev_fill = nullptr;
+  c->push = nullptr;
   for (auto& e : c->prof) e = nullptr;
   for (int i = 0; i < kStages; ++i) c->stage_ms[i] = 0.0;
   c->stage_calls = 0;
@@ -367,6 +472,7 @@ int validate_step(const qsac_ctx* c, const qsac_step_args* a) {
     for (int h = 0; h < c->cfg.n_kv_heads; ++h)
       if (a->res_slot[h] < -1 || a->res_slot[h] >= a->n_res) return QSAC_ERANGE;
   }
+  if (c->push && a->res_slot) return QSAC_EINVAL;  // the transfer threads cannot read HBM sources
   if (c->broken) return QSAC_ESTATE;
   return QSAC_OK;
 }
@@ -381,6 +487,80 @@ void note_fill_sources(qsac_ctx* c, const qsac_step_args* a) {
     c->V_src_host = is_host_memory(a->V_src);
     c->seen_V_src = a->V_src;
   }
+}
+
+// Push mode, before a step is enqueued or replayed: both fill sources must be host memory; a poll that gave up
+// earlier poisons the context; the job of the coming request goes into the ring the transfer threads read.
+int push_submit(qsac_ctx* c, const PushJob& job, bool sources_on_host) {
+  PushEngine* E = c->push;
+  if (!sources_on_host) return QSAC_EINVAL;
+  if (__atomic_load_n(E->box + kPushTimeouts, __ATOMIC_ACQUIRE) != 0) {
+    c->broken = true;
+    return QSAC_ETIMEOUT;
+  }
+  // at most kRing requests ahead of the answers
+  for (int spins = 0; E->submitted + 1 - __atomic_load_n(E->box + kPushFlag2, __ATOMIC_ACQUIRE) >= PushEngine::kRing; ++spins) {
+    if (spins > 100000) return QSAC_ETIMEOUT;  // ten seconds
+    timespec ts = {0, 100000};
+    nanosleep(&ts, nullptr);
+  }
+  E->ring[(E->submitted + 1) % PushEngine::kRing] = job;
+  std::atomic_thread_fence(std::memory_order_release);
+  E->submitted += 1;
+  return QSAC_OK;
+}
+
+PushJob push_job_of(const qsac_ctx* c, const qsac_step_args* a) {
+  PushJob J;
+  J.K_src = static_cast<const char*>(a->K_src);
+  J.V_src = static_cast<const char*>(a->V_src);
+  J.K_slots = static_cast<char*>(a->K_slots);
+  J.V_slots = static_cast<char*>(a->V_slots);
+  J.N = c->cfg.n_ctx;
+  J.k_max = c->cfg.k_max;
+  J.P = c->P;
+  return J;
+}
+
+// Push mode: zeroes the device-side request state and the mailbox flags (nothing may be in flight).
+int push_rewind(qsac_ctx* c) {
+  PushEngine* E = c->push;
+  qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(static_cast<char*>(c->cfg.workspace) + c->L.push), (size_t)4);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(c->s_main));
+  E->box[kPushFlag1] = 0;
+  E->box[kPushFlag2] = 0;
+  E->box[kPushTimeouts] = 0;
+  std::atomic_thread_fence(std::memory_order_seq_cst);
+  return QSAC_OK;
+}
+
+// Push mode: the mailbox in pinned host memory and the transfer threads.  The threads write the cache slots
+// through the device's host-visible memory window, which must span device memory (a "large BAR").
+int push_start(qsac_ctx* c) {
+  int dev = 0, large_bar = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&large_bar, hipDeviceAttributeIsLargeBar, dev));
+  if (!large_bar) return QSAC_EINVAL;
+  PushEngine* E = new (std::nothrow) PushEngine();
+  if (!E) return QSAC_EINVAL;
+  const size_t words = (size_t)kPushHeaderWords + (size_t)c->P + 2 * (size_t)c->P * (size_t)c->cfg.k_max;
+  void* box = nullptr;
+  hipError_t e = hipHostMalloc(&box, words * sizeof(uint32_t), hipHostMallocCoherent);
+  if (e != hipSuccess) {
+    g_last_hip = (int)e;
+    delete E;
+    return QSAC_EHIP;
+  }
+  std::memset(box, 0, words * sizeof(uint32_t));
+  E->box = static_cast<uint32_t*>(box);
+  E->T = c->cfg.push_threads ? c->cfg.push_threads : 4;
+  E->hold = (c->cfg.flags & QSAC_FLAG_PUSH_HOLD) != 0;
+  c->push = E;
+  int rc = push_rewind(c);
+  if (rc != QSAC_OK) return rc;  // qsac_free releases the engine
+  E->start(0);
+  return QSAC_OK;
 }
 
 // Enqueues the launches of one step (also what a graph capture records).  QSAC_EHIP if a HIP call fails,
@@ -459,8 +639,17 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
       qsac_combine_kernel<<<P * G, n_splits > 16 ? 512 : 128, 0, sm>>>(part_ml, part_acc, a->reuse_flags, a->out, Hq, Hkv, G, n_splits,
                                                  L.max_splits, 0);
   };
-  const bool side_attn = c->overlap && !c->fill_kernel;  // reused heads are attended to beside the select
-  const bool side_fill = c->overlap && c->fill_kernel;   // the fill kernel runs beside their attention
+  const bool side_attn = c->overlap && !c->fill_kernel && !c->push;  // reused heads are attended to beside the select
+  const bool side_fill = c->overlap && c->fill_kernel;               // the fill kernel runs beside their attention
+  // push mode: the miss lists go to the host transfer threads, the polling kernel waits for their answer
+  u32* push_state = reinterpret_cast<u32*>(ws + L.push);
+  auto publish = [&]() {
+    qsac_publish_kernel<<<P, 256, 0, sm>>>(miss_count, miss_slot, miss_tok, c->push->box, push_state, k_max, P);
+  };
+  auto poll = [&]() {
+    const unsigned long long us = c->cfg.push_wait_us ? (unsigned long long)c->cfg.push_wait_us : 2000000ull;
+    qsac_poll_kernel<<<1, 64, 0, sm>>>(c->push->box, push_state, us * 100ull);  // 100 ticks per microsecond
+  };
 
   // 2. scores of the missing pairs
   mark(1);
@@ -551,9 +740,20 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
     HIP_TRY(hipStreamWaitEvent(sm, c->ev_fill, 0));
     attend(sm, 2);
     combine();
+  } else if (c->push && !c->profile) {
+    // the transfer runs beside the attention of the pairs that reused their cache
+    publish();
+    attend(sm, 1);
+    poll();
+    attend(sm, 2);
+    combine();
   } else {
     mark(3);
     if (c->fill_kernel) fill_on(sm);
+    if (c->push) {
+      publish();
+      poll();
+    }
     mark(4);
     attend(sm, 0);
     mark(5);
@@ -625,6 +825,10 @@ int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
   if (rc != QSAC_OK) return fail(rc);
   rc = clear_state(c);
   if (rc != QSAC_OK) return fail(rc);
+  if (cfg->flags & QSAC_FLAG_PUSH_FILL) {
+    rc = push_start(c);
+    if (rc != QSAC_OK) return fail(rc);
+  }
   *out = c;
   return QSAC_OK;
 }
@@ -636,6 +840,14 @@ int qsac_reset(qsac_ctx* c) {
     c->steps = 0;
     return QSAC_OK;
   }
+  if (c->push) {
+    // bring the device and the transfer threads back to a common starting point: nothing in flight, sequence 0
+    HIP_TRY(hipStreamSynchronize(c->s_main));
+    c->push->halt();
+    int rc = push_rewind(c);
+    if (rc != QSAC_OK) return rc;
+    c->push->start(0);
+  }
   return clear_state(c);
 }
 
@@ -645,6 +857,10 @@ int qsac_step(qsac_ctx* c, const qsac_step_args* a) {
   if (rc != QSAC_OK) return rc;
   if (!c->dry) {
     note_fill_sources(c, a);
+    if (c->push) {
+      rc = push_submit(c, push_job_of(c, a), c->K_src_host && c->V_src_host);
+      if (rc != QSAC_OK) return rc;
+    }
     rc = enqueue_step(c, a);
     if (rc != QSAC_OK) {
       c->broken = true;  // part of the step may be enqueued: labels and slots can disagree until a reset
@@ -665,6 +881,7 @@ int qsac_graph_capture(qsac_ctx* c, const qsac_step_args* a, qsac_graph** out) {
   if (rc != QSAC_OK) return rc;
   if (!a->dev_params) return QSAC_ENULL;
   note_fill_sources(c, a);
+  if (c->push && !(c->K_src_host && c->V_src_host)) return QSAC_EINVAL;
   qsac_graph* g = new (std::nothrow) qsac_graph();
   if (!g) return QSAC_EINVAL;
   HIP_TRY_OR(hipStreamBeginCapture(c->s_main, hipStreamCaptureModeThreadLocal), delete g);
@@ -691,6 +908,7 @@ int qsac_graph_capture(qsac_ctx* c, const qsac_step_args* a, qsac_graph** out) {
   g->magic = kGraphMagic;
   g->ctx = c;
   g->k = a->k;
+  g->job = push_job_of(c, a);
   *out = g;
   return QSAC_OK;
 }
@@ -700,6 +918,10 @@ int qsac_graph_launch(qsac_graph* g) {
   qsac_ctx* c = g->ctx;
   if (!c || c->magic != kMagic || c->broken) return QSAC_ESTATE;
   if (c->k_bound != 0 && c->k_bound != g->k) return QSAC_ESTATE;
+  if (c->push) {
+    const int rc = push_submit(c, g->job, true);
+    if (rc != QSAC_OK) return rc;
+  }
   const hipError_t e = hipGraphLaunch(g->exec, c->s_main);
   if (e != hipSuccess) {
     g_last_hip = (int)e;
@@ -804,6 +1026,10 @@ int qsac_get_stats(qsac_ctx* c, qsac_stats* out) {
   unsigned long long dev[8];
   HIP_TRY(hipStreamSynchronize(c->s_main));
   HIP_TRY(hipMemcpy(dev, static_cast<char*>(c->cfg.workspace) + c->L.stats, sizeof dev, hipMemcpyDeviceToHost));
+  if (c->push && __atomic_load_n(c->push->box + kPushTimeouts, __ATOMIC_ACQUIRE) != 0) {
+    c->broken = true;
+    return QSAC_ETIMEOUT;  // a polling kernel gave up: the steps since then attended to rows that were not there
+  }
   out->reuse_heads = dev[1];
   out->miss_heads = dev[2];
   out->slot_hits = dev[3];
@@ -830,6 +1056,13 @@ int qsac_get_stage_ms(qsac_ctx* c, double* ms_sum, uint64_t* n_steps) {
 
 int qsac_free(qsac_ctx* c) {
   if (!c || c->magic != kMagic) return QSAC_ESTATE;
+  if (c->push) {
+    (void)hipStreamSynchronize(c->s_main);  // no polling kernel may still be waiting for the threads
+    c->push->halt();
+    if (c->push->box) (void)hipHostFree(c->push->box);
+    delete c->push;
+    c->push = nullptr;
+  }
   if (!c->dry) {
     if (c->ev_sel) (void)hipEventDestroy(c->ev_sel);
     if (c->ev_fill) (void)hipEventDestroy(c->ev_fill);
@@ -851,6 +1084,7 @@ const char* qsac_strerror(int code) {
     case QSAC_EHIP: return "HIP runtime call failed";
     case QSAC_ESTATE: return "bad handle, call out of order, or the context needs qsac_reset after a failed step";
     case QSAC_EALIGN: return "pointer is not 16-byte aligned";
+    case QSAC_ETIMEOUT: return "push mode: a polling kernel gave up waiting for the host transfer threads";
     default: return "unknown error";
   }
 }

@@ -1329,6 +1329,75 @@ __global__ __launch_bounds__(256) void qsac_fill_kernel(const int* __restrict__ 
     }
 }
 
+// ---------------------------------------------------------------- push-mode transfer
+
+// Push mode (Section 5.2 of the paper, GPU-centric synchronization; Section 6.2, zero-copy transfer engine): the
+// GPU hands the compacted miss lists to host transfer threads through a mailbox in pinned host memory and a
+// request flag (the paper's Flag1); the threads copy the rows into the cache slots and answer with a completion
+// flag (Flag2), which a polling kernel waits for.  Mailbox layout (32-bit words): flag1 at word 0, flag2 at word
+// 16, the count of polls that gave up at word 32 (each on a cache line of its own), then count[P], slot[P][k_max],
+// tok[P][k_max] from word kPushHeaderWords on.
+constexpr int kPushFlag1 = 0, kPushFlag2 = 16, kPushTimeouts = 32, kPushHeaderWords = 64;
+
+// One workgroup per pair copies the pair's miss list into the mailbox.  The last workgroup to finish takes the
+// next sequence number and publishes it as Flag1.  state: [0] sequence number of the last request, [1] workgroups
+// done in this launch, [2] polls that gave up.
+__global__ __launch_bounds__(256) void qsac_publish_kernel(const int* __restrict__ miss_count,
+                                                           const int* __restrict__ miss_slot,
+                                                           const int* __restrict__ miss_tok, u32* __restrict__ box,
+                                                           u32* __restrict__ state, int k_max, int P) {
+  const int p = blockIdx.x;
+  const int m = miss_count[p];
+  int* h_count = reinterpret_cast<int*>(box + kPushHeaderWords);
+  int* h_slot = h_count + P + (size_t)p * k_max;
+  int* h_tok = h_count + P + (size_t)P * k_max + (size_t)p * k_max;
+  const int* ms = miss_slot + (size_t)p * k_max;
+  const int* mt = miss_tok + (size_t)p * k_max;
+  for (int i = threadIdx.x; i < m; i += 256) {
+    h_slot[i] = ms[i];
+    h_tok[i] = mt[i];
+  }
+  if (threadIdx.x == 0) h_count[p] = m;
+  // every store of this workgroup has been acknowledged by the memory system before it counts itself done
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const u32 done = atomicAdd(&state[1], 1u);
+    if (done == (u32)P - 1) {
+      state[1] = 0;
+      const u32 seq = state[0] + 1;
+      state[0] = seq;
+      __hip_atomic_store(box + kPushFlag1, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+  }
+}
+
+// Waits until the host has answered the last request (Flag2 has reached its sequence number), for at most
+// budget_ticks of the constant 100-MHz clock.  Giving up is recorded in state[2] and in the mailbox; either way
+// the kernel ends, so the stream never hangs on a host that does not answer.
+__global__ __launch_bounds__(64) void qsac_poll_kernel(u32* __restrict__ box, u32* __restrict__ state,
+                                                       unsigned long long budget_ticks) {
+  if (threadIdx.x != 0) return;
+  const u32 want = state[0];
+  const unsigned long long t0 = wall_clock64();
+  bool ok = false;
+  for (;;) {
+    const u32 f = __hip_atomic_load(box + kPushFlag2, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM);
+    if ((int)(f - want) >= 0) {
+      ok = true;
+      break;
+    }
+    if (wall_clock64() - t0 > budget_ticks) break;
+    __builtin_amdgcn_s_sleep(16);
+  }
+  if (!ok) {
+    const u32 n = state[2] + 1;
+    state[2] = n;
+    __hip_atomic_store(box + kPushTimeouts, n, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+}
+
 // ---------------------------------------------------------------- attention
 
 // which: 0 = every pair, 1 = pairs that reused, 2 = pairs that missed.

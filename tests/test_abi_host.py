@@ -80,11 +80,17 @@ def test_workspace_size_and_layout(lib):
     (dict(Hkv=65, Hq=65), Q.QSAC_ERANGE),
     (dict(flags=1 << 20), Q.QSAC_EINVAL),
     (dict(importance=[1, 1, 1, 0, 1, 1, 1, 1]), Q.QSAC_EINVAL),
+    (dict(flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_PUSH_HOLD), Q.QSAC_EINVAL),                         # hold without push mode
+    (dict(flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_PUSH_FILL | Q.QSAC_FLAG_FILL_KERNEL), Q.QSAC_EINVAL),  # two ways to fill
+    (dict(flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_PUSH_FILL, push_threads=65), Q.QSAC_ERANGE),
+    (dict(flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_PUSH_FILL, push_wait_us=-1), Q.QSAC_ERANGE),
 ])
 def test_bad_configs_are_rejected(lib, kw, code):
-    a = dict(B=1, Hq=8, Hkv=2, N=4096, k_max=256, dtype=Q.QSAC_F16, flags=Q.QSAC_FLAG_DRY_RUN, importance=None, D=128)
+    a = dict(B=1, Hq=8, Hkv=2, N=4096, k_max=256, dtype=Q.QSAC_F16, flags=Q.QSAC_FLAG_DRY_RUN, importance=None, D=128,
+             push_threads=0, push_wait_us=0)
     a.update(kw)
-    cfg = Q.make_config(a["B"], a["Hq"], a["Hkv"], a["N"], a["k_max"], a["dtype"], a["flags"], a["importance"])
+    cfg = Q.make_config(a["B"], a["Hq"], a["Hkv"], a["N"], a["k_max"], a["dtype"], a["flags"], a["importance"],
+                        push_threads=a["push_threads"], push_wait_us=a["push_wait_us"])
     cfg.head_dim = a["D"]
     assert Q.qsac_workspace_bytes(cfg) == 0
     ctx = C.c_void_p()
