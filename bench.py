@@ -284,6 +284,14 @@ class Bench:
                     res["overlap"] = {"serial_us": 1e6 * t_ser / K_steps, "side_stream_us": 1e6 * t_ovl / K_steps,
                                       "fill_us": uf["fill"],
                                       "efficiency": (t_ser - t_ovl) / K_steps * 1e6 / uf["fill"] if uf["fill"] else None}
+                    if w.host_k and w.host_v and not (single and a.resident):
+                        # the paper's push mode as the A/B: host threads write the rows into the slots, the GPU polls
+                        t_push, dpush = timed(Q.QSAC_FLAG_PUSH_FILL)
+                        up, dp_ = profile(tau, W_steps, K_steps, extra=Q.QSAC_FLAG_PUSH_FILL)
+                        res["push"] = {"steps_per_s": K_steps / t_push, "us_per_step": 1e6 * t_push / K_steps,
+                                       "transfer_us": up["fill"], "GBps": dp_["bytes_filled_host"] / up["fill"] / 1e3,
+                                       "frac": dp_["bytes_filled_host"] / up["fill"] / 1e3 / peak,
+                                       "pull_us_per_step": res["ms_per_step"] * 1e3, "threads": 4}
             if (detail != "brief" or name in ("tiny", "llama3_8b_32k")) and not (single and (a.decode_buffers or a.resident)):
                 res["graph"] = self.graph_leg(session, q_dev, tau, w, K_steps, W_steps)
 
@@ -471,6 +479,8 @@ def brief(res):
             o["fill"]["fill_kernel_frac"] = r4(p["fill_kernel_GBps"] / p["peak_GBps"])
     if "overlap" in res:
         o["overlap"] = {k: r4(v) for k, v in res["overlap"].items()}
+    if "push" in res:
+        o["push"] = {k: r4(v) for k, v in res["push"].items()}
     if "graph" in res:
         o["graph"] = {k: r4(v) for k, v in res["graph"].items()}
     if "cpu_baseline" in res:
@@ -531,7 +541,7 @@ def main():
         line["all_miss"] = {"stage_us": {s: r4(head["all_miss"]["stage_us"][s]) for s in STAGES},
                             "score_frac": r4(head["all_miss"]["score_GBps"] / HBM_PEAK_GBS),
                             "attn_frac": r4(head["all_miss"]["attn_GBps"] / HBM_PEAK_GBS)}
-        for key in ("overlap", "graph"):
+        for key in ("overlap", "push", "graph"):
             if key in head:
                 line[key] = {k: r4(v) for k, v in head[key].items()}
     if "read_only_launch" in head:

@@ -135,6 +135,7 @@ struct PushJob {
 struct PushEngine {
   static constexpr uint32_t kRing = 1024;  // requests the host may be ahead of the device
   uint32_t* box = nullptr;                 // mailbox in pinned host memory (layout: qsac_publish_kernel)
+  volatile uint32_t* hdp_flush = nullptr;  // the device's host-data-path flush register, mapped into this process
   int T = 0;
   bool hold = false;
   std::vector<std::thread> threads;
@@ -179,7 +180,6 @@ struct PushEngine {
       // thread `id` takes the rows [lo, hi) of all pairs' lists laid end to end
       const long lo = total * id / T, hi = total * (id + 1) / T;
       long base = 0;
-      const volatile uint32_t* last = nullptr;
       for (int p = 0; p < J.P && base < hi; ++p) {
         const long c = count[p];
         if (base + c > lo) {
@@ -193,15 +193,18 @@ struct PushEngine {
           for (long e = e0; e < e1; ++e) {
             std::memcpy(Kd + (size_t)sp[e] * 256, Ks + (size_t)tp[e] * 256, 256);
             std::memcpy(Vd + (size_t)sp[e] * 256, Vs + (size_t)tp[e] * 256, 256);
-            last = reinterpret_cast<const volatile uint32_t*>(Vd + (size_t)sp[e] * 256);
           }
         }
         base += c;
       }
-      _mm_sfence();
-      // a read through the same window cannot overtake the writes before it: once it returns they are in device memory
-      if (last) (void)*last;
+      _mm_sfence();  // this thread's write-combined stores have left the core
       if (arrived.fetch_add(1, std::memory_order_acq_rel) == T - 1) {
+        // Last thread of the request.  Host writes travel through the device's host data path, which may hold them
+        // back from device memory: flush it (the register write follows the row writes on the bus), then read
+        // through the same window, which cannot return before the writes ahead of it have arrived.
+        if (hdp_flush) *hdp_flush = 1u;
+        _mm_sfence();
+        (void)*reinterpret_cast<const volatile uint32_t*>(J.K_slots);
         arrived.store(0, std::memory_order_relaxed);
         __atomic_store_n(box + qsac::kPushFlag2, seq, __ATOMIC_RELEASE);  // the paper's Flag2
       }
@@ -554,6 +557,13 @@ int push_start(qsac_ctx* c) {
   }
   std::memset(box, 0, words * sizeof(uint32_t));
   E->box = static_cast<uint32_t*>(box);
+  {
+    uint32_t* reg = nullptr;  // the attribute is pointer-sized: address of the HDP_MEM_COHERENCY_FLUSH_CNTL register
+    if (hipDeviceGetAttribute(reinterpret_cast<int*>(&reg), hipDeviceAttributeHdpMemFlushCntl, dev) == hipSuccess)
+      E->hdp_flush = reg;
+    else
+      (void)hipGetLastError();
+  }
   E->T = c->cfg.push_threads ? c->cfg.push_threads : 4;
   E->hold = (c->cfg.flags & QSAC_FLAG_PUSH_HOLD) != 0;
   c->push = E;

@@ -1405,34 +1405,34 @@ __device__ __forceinline__ bool pair_selected(int which, const uint8_t* reuse_fl
   return which == 0 || (which == 1) == (reuse_flags[p] != 0);
 }
 
-// Workgroup (split, pair): slots [split*rows, split*rows + rows) of the pair, all G query heads.
+// Workgroup (split, pair): slots [split*rows, split*rows + rows) of the pair, all G query heads; both
+// contractions of softmax(q K_c^T / sqrt(d)) V_c (Section 2.1 of the paper) run on the matrix cores.
 // Wave w takes the 16-slot tiles w, w+4, ... of the range.  Per tile:
-//   - K and V rows arrive by fully coalesced loads (lane l: row 4j + l/16 of the tile, 16-byte
-//     piece l%16, j = 0..3); the next tile's loads are in flight while this one is consumed;
-//   - the K tile goes through a wave-private LDS tile into four v_mfma_f32_16x16x32 against the
-//     zero-padded query group (as in the scoring kernel): lane l then holds the logits of slot
-//     l%16 for queries 4*(l/16) .. +3;
-//   - those lanes do the online softmax for their queries (tile maximum by DPP over the 16
-//     slots, one exp per logit), and publish the 16 x G weights and the G rescale factors in
-//     LDS;
-//   - every lane folds its four V rows (8 channels each) into acc[g][8] with plain FMAs, reading
-//     its rows' weights back from LDS.
-// All lanes of a wave share the running maxima, so the four row groups add up without
-// rescaling; waves are merged through LDS.  The split's (max, sum, unnormalised output) goes to
-// the workspace for qsac_combine_kernel, or, when the pair has a single split, the output is
-// written directly.
+//   - K and V rows arrive by fully coalesced loads (lane l: row 4j + l/16 of the tile, 16-byte piece
+//     l%16, j = 0..3) and are parked in two wave-private LDS tiles;
+//   - logits, transposed: S^T = K Q^T with the K tile as the A operand (row = slot) and the zero-padded
+//     query group as the B operand (column = query), four v_mfma_f32_16x16x32.  Lane l then holds, for
+//     query l%16, the logits of slots 4*(l/16) .. +3: exactly where the B operand of the second product
+//     wants that query's weights, so the weights never move between lanes;
+//   - online softmax per lane (its query; tile maximum over the four lanes that share the query);
+//   - O^T += V^T P, eight v_mfma_f32_16x16x32, one per block of 16 channels: the A operand (row =
+//     channel, contraction over slots) comes out of the V tile through the transposing LDS load
+//     (ds_read_b64_tr_b16); the B operand holds each weight twice, as hi + lo 16-bit parts (the
+//     contraction index runs over 16 slots x {hi, lo}), which keeps 16 significant bits of every
+//     weight: a weight rounded to one bfloat16 would cost up to 0.4 % of a dominant V row.
+// acc[blk][r] of lane l is channel 16 blk + 4 (l/16) + r of query l%16; lanes with l%16 >= G carry
+// zero padding.  Waves are merged through LDS; the split's (max, sum, unnormalised output) goes to
+// the workspace for qsac_combine_kernel, or, when the pair has a single split, the output is written
+// directly.
+//
+// The next tile's loads are in flight while the current one is consumed.
 //
 // FETCH ("fill on read"): a slot whose entry in fetch_tok is a token (>= 0) has no row yet: its
 // K and V rows are read from the fill sources instead of the slot and written into the slot on
 // the way, so the miss fill costs no pass of its own.  Each slot belongs to exactly one lane
 // of one workgroup per 16-byte piece, so nothing else reads or writes it during the launch.
-__device__ __forceinline__ float row16_max(float v) {
-  v = fmaxf(v, dpp_move<0xB1>(v));
-  v = fmaxf(v, dpp_move<0x4E>(v));
-  v = fmaxf(v, dpp_move<0x141>(v));
-  v = fmaxf(v, dpp_move<0x140>(v));
-  return v;
-}
+typedef __attribute__((ext_vector_type(4))) short s4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t v2u;
 
 struct AttnArgs {
   const uint16_t* q;
@@ -1454,30 +1454,50 @@ struct AttnArgs {
 // LDS of one attention workgroup of NW waves
 template <int G, int NW>
 struct AttnLds {
-  static constexpr int GP = G > 4 ? 8 : 4;  // queries padded to whole lane quarters
-  alignas(16) unsigned char tile[NW][16 * kTilePitch];
-  alignas(16) float p[NW][16][GP];
-  alignas(16) float alpha[NW][GP];
+  alignas(16) unsigned char ktile[NW][16 * kTilePitch];
+  alignas(16) unsigned char vtile[NW][16 * kTilePitch];
   float ml[NW][G][2];
   float acc[NW][G][kD];
 };
+
+// 16 slots x 16 channels of an LDS tile as the A operand of a product whose rows are channels and whose
+// contraction runs over slots: lane (i = l%16, g = l/16) receives channel c0 + i of slots 4g .. 4g+3.
+// The transposing load hands lane 16g + i element i%4 of the 8-byte chunks addressed by lanes
+// 16g + i/4 + 4r (r = 0..3) of its group; so lane 16g + s addresses slot 4g + s/4, channels
+// c0 + 4(s%4) .. +3.
+__device__ __forceinline__ v2u lds_read_tr16(const unsigned char* tile, int c0, int lane) {
+  const int g = lane >> 4, s = lane & 15;
+  const unsigned char* ptr = tile + (4 * g + (s >> 2)) * kTilePitch + (c0 + 4 * (s & 3)) * 2;
+  const s4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4_t __attribute__((address_space(3)))*)ptr);
+  return __builtin_bit_cast(v2u, r);
+}
+
+// A softmax weight p in [0, 1] as two 16-bit floats of the tile's type with hi + lo = p to 16 (bfloat16) or 22
+// (binary16) significant bits.
+template <int DT>
+__device__ __forceinline__ void split16(float p, u32& hi, u32& lo) {
+  if (DT == 0) {
+    const _Float16 h = (_Float16)p;
+    const _Float16 l = (_Float16)(p - (float)h);
+    hi = __builtin_bit_cast(uint16_t, h);
+    lo = __builtin_bit_cast(uint16_t, l);
+  } else {
+    const u32 u = fbits(p);
+    hi = u >> 16;  // truncated: the remainder is non-negative and exact in fp32
+    const float rem = p - bitsf(u & 0xffff0000u);
+    lo = (fbits(rem) + 0x8000u) >> 16;  // rounded to nearest
+  }
+}
 
 // The work of one attention workgroup of NW waves (all of its threads call this).
 template <int DT, int G, bool FETCH, int NW>
 __device__ __forceinline__ void attn_body(const AttnArgs& A, const FillSrc& src, int p, int split,
                                           AttnLds<G, NW>& S) {
-  constexpr int GP = AttnLds<G, NW>::GP;
   constexpr int kStep = NW * 16;  // slots between two tiles of a wave
-  const uint16_t* __restrict__ q = A.q;
   v4u* __restrict__ K_slots = A.K_slots;
   v4u* __restrict__ V_slots = A.V_slots;
-  const int* __restrict__ fetch_tok = A.fetch_tok;
-  const int* __restrict__ miss_count = A.miss_count;
   float* __restrict__ part_ml = A.part_ml;
   float* __restrict__ part_acc = A.part_acc;
-  float* __restrict__ out = A.out;
-  const v4u* __restrict__ K_app = A.K_app;
-  const v4u* __restrict__ V_app = A.V_app;
   const int64_t N = A.N;
   // a replayed step reads the row count of the append-only buffer from device memory; the launch is sized for
   // A.n_app rows, and the splits past the valid rows contribute empty partials
@@ -1487,7 +1507,7 @@ __device__ __forceinline__ void attn_body(const AttnArgs& A, const FillSrc& src,
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = lane & 15, quarter = lane >> 4;
   const int b = p / Hkv, h = p % Hkv;
-  const v4u* qg = reinterpret_cast<const v4u*>(q + ((size_t)b * Hq + (size_t)h * G) * kD);
+  const v4u* qg = reinterpret_cast<const v4u*>(A.q + ((size_t)b * Hq + (size_t)h * G) * kD);
   v4u qa[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) qa[j] = (m < G) ? qg[m * kRowU4 + quarter * 4 + j] : v4u{0, 0, 0, 0};
@@ -1495,29 +1515,24 @@ __device__ __forceinline__ void attn_body(const AttnArgs& A, const FillSrc& src,
   v4u* Vp = V_slots + (size_t)p * k_max * kRowU4;
   const v4u *Ks, *Vs;
   fill_rows_of(src, p, Hkv, N, Ks, Vs);
-  const int* ft = fetch_tok + (size_t)p * k_max;
-  const bool fetch = FETCH && miss_count[p] > 0;  // uniform over the workgroup
+  const int* ft = A.fetch_tok + (size_t)p * k_max;
+  const bool fetch = FETCH && A.miss_count[p] > 0;  // uniform over the workgroup
   // Rows k .. k + n_app - 1 of the attended set are the valid rows of the append-only buffer (KV of
   // the tokens generated during decoding, Sections 6.1 and 6.2 of the paper), read in place.
-  const v4u* Ka = K_app + (size_t)p * app_cap * kRowU4;
-  const v4u* Va = V_app + (size_t)p * app_cap * kRowU4;
+  const v4u* Ka = A.K_app + (size_t)p * app_cap * kRowU4;
+  const v4u* Va = A.V_app + (size_t)p * app_cap * kRowU4;
 
   const float kScale = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
   const float kNegInf = -__builtin_inff();
-  float mrun[4], lrun[4];  // queries 4*quarter + i: running maximum (log2 domain), this lane's share of the sum
-  float acc[G][8];         // channels 8m .. 8m+7 of every query, over the rows of this lane's row group
+  // this lane: query m, slots 4*quarter .. +3 of every tile
+  float mrun = kNegInf, lrun = 0.f;  // running maximum (log2 domain), this lane's share of the sum
+  f4_t acc[8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    mrun[i] = kNegInf;
-    lrun[i] = 0.f;
-  }
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int d = 0; d < 8; ++d) acc[g][d] = 0.f;
+  for (int i = 0; i < 8; ++i) acc[i] = f4_t{0.f, 0.f, 0.f, 0.f};
 
   const int s_begin = split * rows;
   const int s_end = min(s_begin + rows, k + n_app);
+  const int tw = s_begin + wave * 16;  // uniform over the wave: every lane takes part in the MFMAs
 
   // tokens to fetch for this lane's four rows of the tile at t0 (-1: the row is in its slot).
   // Rows past the end of the range repeat the last row, so that what is loaded is always real data.
@@ -1529,171 +1544,156 @@ __device__ __forceinline__ void attn_body(const AttnArgs& A, const FillSrc& src,
       tok[j] = (fetch && row < k) ? ft[row] : -1;
     }
   };
-  // issue the loads of this lane's four K (or V) rows of the tile at t0
-  auto load_tile = [&](int t0, const int (&tok)[4], v4u (&dst)[4], const v4u* slots, const v4u* src,
+  // issue the loads of this lane's four K (or V) rows of the tile at t0.  Slot rows are streamed (read once per
+  // step); rows that come from the fill source keep plain loads: they often still sit in the last-level cache
+  // after the scoring pass.
+  auto load_tile = [&](int t0, const int (&tok)[4], v4u (&dst)[4], const v4u* slots, const v4u* from_src,
                        const v4u* app) {
+    if (FETCH && fetch) {  // uniform: a pair that reused never looks at tokens
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int row = t0 + 4 * j + quarter;
-      row = row < s_end ? row : s_end - 1;
-      const v4u* from = row < k ? slots + (size_t)row * kRowU4 : app + (size_t)(row - k) * kRowU4;
-      if (FETCH && tok[j] >= 0)
-        dst[j] = src[(size_t)tok[j] * kRowU4 + m];
-      else
+      for (int j = 0; j < 4; ++j) {
+        int row = t0 + 4 * j + quarter;
+        row = row < s_end ? row : s_end - 1;
+        const v4u* from = row < k ? slots + (size_t)row * kRowU4 : app + (size_t)(row - k) * kRowU4;
+        if (tok[j] >= 0)
+          dst[j] = from_src[(size_t)tok[j] * kRowU4 + m];
+        else
+          dst[j] = __builtin_nontemporal_load(from + m);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        int row = t0 + 4 * j + quarter;
+        row = row < s_end ? row : s_end - 1;
+        const v4u* from = row < k ? slots + (size_t)row * kRowU4 : app + (size_t)(row - k) * kRowU4;
         dst[j] = __builtin_nontemporal_load(from + m);
+      }
     }
   };
-  // fetched rows go into their slots
-  auto store_fetched = [&](int t0, const int (&tok)[4], const v4u (&val)[4], v4u* slots) {
-    if (FETCH) {
+  // fetched rows go into their slots; the tile goes into LDS
+  auto stage = [&](int t0, const int (&tok)[4], const v4u (&val)[4], v4u* slots, unsigned char* tile) {
+    if (FETCH && fetch) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int row = t0 + 4 * j + quarter;
         if (tok[j] >= 0 && row < s_end) slots[(size_t)row * kRowU4 + m] = val[j];
       }
     }
-  };
-  // K tile -> LDS -> logits -> online softmax -> weights and rescale factors in LDS
-  auto stage_k = [&](const v4u (&kk)[4]) {
-    unsigned char* tile = S.tile[wave];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) *reinterpret_cast<v4u*>(tile + (4 * j + quarter) * kTilePitch + m * 16) = kk[j];
+    for (int j = 0; j < 4; ++j) *reinterpret_cast<v4u*>(tile + (4 * j + quarter) * kTilePitch + m * 16) = val[j];
     __builtin_amdgcn_wave_barrier();
   };
+  unsigned char* ktile = S.ktile[wave];
+  unsigned char* vtile = S.vtile[wave];
+  v4u pb;    // this tile's weights as the B operand of the second product
+  float al;  // this tile's rescale factor of what has been accumulated so far
+  // K tile in LDS -> logits -> online softmax
   auto softmax_tile = [&](int t0) {
-    const unsigned char* tile = S.tile[wave];
     f4_t sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const v4u kb = *reinterpret_cast<const v4u*>(tile + m * kTilePitch + (quarter * 4 + j) * 16);
-      sc = mfma16<DT>(qa[j], kb, sc);
+      const v4u kb = *reinterpret_cast<const v4u*>(ktile + m * kTilePitch + (quarter * 4 + j) * 16);
+      sc = mfma16<DT>(kb, qa[j], sc);
     }
-    // sc[i]: logit of query 4*quarter + i against slot t0 + m
-    const bool slot_ok = t0 + m < s_end;
-    f4_t pw, al;
+    // sc[r]: logit of slot t0 + 4*quarter + r for query m
+    float sv[4];
+    float tmax = kNegInf;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float sv = slot_ok ? sc[i] * kScale : kNegInf;
-      const float mnew = fmaxf(mrun[i], row16_max(sv));  // finite: slot t0 is real
-      al[i] = (mrun[i] == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mrun[i] - mnew);
-      pw[i] = slot_ok ? __builtin_amdgcn_exp2f(sv - mnew) : 0.f;
-      lrun[i] = lrun[i] * al[i] + pw[i];
-      mrun[i] = mnew;
+    for (int r = 0; r < 4; ++r) {
+      sv[r] = (t0 + 4 * quarter + r < s_end) ? sc[r] * kScale : kNegInf;
+      tmax = fmaxf(tmax, sv[r]);
     }
-    if (quarter * 4 < GP) {
-      *reinterpret_cast<f4_t*>(&S.p[wave][m][quarter * 4]) = pw;
-      if (m == 0) *reinterpret_cast<f4_t*>(&S.alpha[wave][quarter * 4]) = al;
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));  // finite: slot t0 is real
+    const float mnew = fmaxf(mrun, tmax);
+    al = (mrun == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mrun - mnew);
+    u32 hi[4], lo[4];
+    float psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float pw = (sv[r] == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(sv[r] - mnew);
+      psum += pw;
+      split16<DT>(pw, hi[r], lo[r]);
     }
-    __builtin_amdgcn_wave_barrier();
+    lrun = lrun * al + psum;
+    mrun = mnew;
+    pb = v4u{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
   };
-  // acc <- acc * alpha + sum over this lane's four rows of weight * V row
-  auto fold_v = [&](const v4u (&vv)[4]) {
-    float a[GP];
-    *reinterpret_cast<f4_t*>(&a[0]) = *reinterpret_cast<const f4_t*>(&S.alpha[wave][0]);
-    if (GP > 4) *reinterpret_cast<f4_t*>(&a[4]) = *reinterpret_cast<const f4_t*>(&S.alpha[wave][4]);
+  // V tile in LDS -> O^T <- O^T * alpha + V^T [P_hi ; P_lo]
+  auto fold_v = [&]() {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+    for (int blk = 0; blk < 8; ++blk) {
+      const v2u vt = lds_read_tr16(vtile, 16 * blk, lane);
+      const v4u va = {vt.x, vt.y, vt.x, vt.y};  // V^T against the hi parts, then against the lo parts
+      f4_t c = acc[blk];
 #pragma unroll
-      for (int d = 0; d < 8; ++d) acc[g][d] *= a[g];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      float pr[GP];
-      *reinterpret_cast<f4_t*>(&pr[0]) = *reinterpret_cast<const f4_t*>(&S.p[wave][4 * j + quarter][0]);
-      if (GP > 4) *reinterpret_cast<f4_t*>(&pr[4]) = *reinterpret_cast<const f4_t*>(&S.p[wave][4 * j + quarter][4]);
-      const u32 w[4] = {vv[j].x, vv[j].y, vv[j].z, vv[j].w};
-      float vf[8];
-#pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        vf[2 * d] = lo16<DT>(w[d]);
-        vf[2 * d + 1] = hi16<DT>(w[d]);
-      }
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int d = 0; d < 8; ++d) acc[g][d] = fmaf(pr[g], vf[d], acc[g][d]);
+      for (int r = 0; r < 4; ++r) c[r] *= al;
+      acc[blk] = mfma16<DT>(va, pb, c);
     }
     __builtin_amdgcn_wave_barrier();
   };
 
   {
-    // One K and one V register set: the next tile's K loads are issued as soon as this tile's K
-    // sits in LDS, the next V loads as soon as this tile's V is folded in.  Tokens run one tile
-    // further ahead.
-    int tokC[4], tokN[4];
+    // One K and one V register set: the next tile's K loads are issued as soon as this tile's K sits in LDS,
+    // the next V loads as soon as this tile's V does.  Tokens run one tile further ahead.
+    int tokC[4] = {-1, -1, -1, -1}, tokN[4] = {-1, -1, -1, -1};
     v4u kk[4], vv[4];
-    int t0 = s_begin + wave * 16;  // uniform over the wave: every lane takes part in the MFMAs and DPP
+    int t0 = tw;
     if (t0 < s_end) {
-      load_tok(t0, tokC);
+      if (FETCH && fetch) load_tok(t0, tokC);
       load_tile(t0, tokC, kk, Kp, Ks, Ka);
       load_tile(t0, tokC, vv, Vp, Vs, Va);
-      if (t0 + kStep < s_end) load_tok(t0 + kStep, tokN);
+      if (FETCH && fetch && t0 + kStep < s_end) load_tok(t0 + kStep, tokN);
     }
     for (; t0 < s_end; t0 += kStep) {
       const bool more = t0 + kStep < s_end;
-      store_fetched(t0, tokC, kk, Kp);
-      stage_k(kk);
+      stage(t0, tokC, kk, Kp, ktile);
       if (more) load_tile(t0 + kStep, tokN, kk, Kp, Ks, Ka);
       softmax_tile(t0);
-      store_fetched(t0, tokC, vv, Vp);
-      fold_v(vv);
+      stage(t0, tokC, vv, Vp, vtile);
       if (more) {
         load_tile(t0 + kStep, tokN, vv, Vp, Vs, Va);
+        if (FETCH && fetch) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) tokC[j] = tokN[j];
-        if (t0 + 2 * kStep < s_end) load_tok(t0 + 2 * kStep, tokN);
+          for (int j = 0; j < 4; ++j) tokC[j] = tokN[j];
+          if (t0 + 2 * kStep < s_end) load_tok(t0 + 2 * kStep, tokN);
+        }
       }
+      fold_v();
     }
   }
 
-  // the four row groups of the wave hold different rows under the same maxima: add them up
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int d = 0; d < 8; ++d) {
-      float v = acc[g][d];
-      v += __shfl_xor(v, 16);
-      v += __shfl_xor(v, 32);
-      acc[g][d] = v;
+  // the four lanes of a query hold different slots under the same maximum
+  lrun += __shfl_xor(lrun, 16);
+  lrun += __shfl_xor(lrun, 32);
+  if (m < G) {
+    if (quarter == 0) {
+      S.ml[wave][m][0] = mrun;
+      S.ml[wave][m][1] = lrun;
     }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) lrun[i] = row16_sum(lrun[i]);
-  if (m == 0 && quarter * 4 < GP) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int g = quarter * 4 + i;
-      if (g < G) {
-        S.ml[wave][g][0] = mrun[i];
-        S.ml[wave][g][1] = lrun[i];
-      }
-    }
-  }
-  if (quarter == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int d = 0; d < 8; ++d) S.acc[wave][g][m * 8 + d] = acc[g][d];
+    for (int blk = 0; blk < 8; ++blk) *reinterpret_cast<f4_t*>(&S.acc[wave][m][16 * blk + 4 * quarter]) = acc[blk];
   }
   __syncthreads();
-  const int b_out = p / Hkv, h_out = p % Hkv;
-  float* out_p = out + ((size_t)b_out * Hq + (size_t)h_out * G) * kD;
+  float* out_p = A.out + ((size_t)b * Hq + (size_t)h * G) * kD;
   for (int i = threadIdx.x; i < G * kD; i += NW * 64) {
     const int g = i >> 7, d = i & 127;
     float M = kNegInf;
 #pragma unroll
     for (int w = 0; w < NW; ++w) M = fmaxf(M, S.ml[w][g][0]);
-    float L = 0.f, A = 0.f;
+    float L = 0.f, Acc = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
       const float mw = S.ml[w][g][0];
       const float wt = (mw == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
       L += S.ml[w][g][1] * wt;
-      A += S.acc[w][g][d] * wt;
+      Acc += S.acc[w][g][d] * wt;
     }
     if (n_splits == 1) {
-      out_p[i] = A / L;
+      out_p[i] = Acc / L;
     } else {
       const size_t slot = ((size_t)p * G + g) * max_splits + split;
-      part_acc[slot * kD + d] = A;
+      part_acc[slot * kD + d] = Acc;
       if (d == 0) {
         part_ml[slot * 2 + 0] = M;
         part_ml[slot * 2 + 1] = L;
