@@ -156,6 +156,13 @@ class Bench:
             K_host = torch.empty(K_dev.shape, dtype=K_dev.dtype, pin_memory=w.host_k).copy_(K_dev)
         if w.host_v or want_cpu:
             V_host = torch.empty(V_dev.shape, dtype=V_dev.dtype, pin_memory=w.host_v).copy_(V_dev)
+        for t in (K_host, V_host):
+            if t is not None and t.is_pinned():
+                # The store was filled by a device copy: the host's own page-table entries for it do not exist yet, and
+                # the first host access to each page would fault them in (tens of microseconds per 64 KiB here).  A
+                # host KV store written by the host has them; touch every page once so the push-mode transfer
+                # threads, which read it from the host, are not timed on page faults.
+                t.view(-1)[::2048].float().sum().item()
         K_src = K_host if w.host_k else K_dev
         V_src = V_host if w.host_v else V_dev
         chain = W.chain_for(w)

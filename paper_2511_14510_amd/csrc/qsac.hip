@@ -142,7 +142,24 @@ struct PushEngine {
   std::atomic<bool> stop{false};
   std::atomic<int> arrived{0};
   uint32_t submitted = 0;  // sequence number of the last request whose job is in the ring (host thread of the caller)
+  const char *mapped_K = nullptr, *mapped_V = nullptr;  // slot tensors whose window pages have been touched
   PushJob ring[kRing];
+
+  // The first host access to a page of the device memory window faults its mapping in, which costs tens of
+  // microseconds per page here: touch every page of a slot tensor once (a read; the contents stay), with all
+  // the threads, before the first request that writes into it, so that no polling kernel waits for page faults.
+  void map_window(const char* base, size_t bytes) {
+    std::vector<std::thread> th;
+    const int n = T > 0 ? T : 1;
+    for (int i = 0; i < n; ++i)
+      th.emplace_back([=] {
+        const size_t lo = bytes * i / n / 4096 * 4096, hi = bytes * (i + 1) / n;
+        unsigned acc = 0;
+        for (size_t off = lo; off < hi; off += 4096) acc += *reinterpret_cast<const volatile unsigned char*>(base + off);
+        (void)acc;
+      });
+    for (auto& t : th) t.join();
+  }
 
   void start(uint32_t seq_now) {
     stop.store(false);
@@ -506,6 +523,15 @@ int push_submit(qsac_ctx* c, const PushJob& job, bool sources_on_host) {
     if (spins > 100000) return QSAC_ETIMEOUT;  // ten seconds
     timespec ts = {0, 100000};
     nanosleep(&ts, nullptr);
+  }
+  const size_t slot_bytes = (size_t)job.P * (size_t)job.k_max * 256;
+  if (job.K_slots != E->mapped_K) {
+    E->map_window(job.K_slots, slot_bytes);
+    E->mapped_K = job.K_slots;
+  }
+  if (job.V_slots != E->mapped_V) {
+    E->map_window(job.V_slots, slot_bytes);
+    E->mapped_V = job.V_slots;
   }
   E->ring[(E->submitted + 1) % PushEngine::kRing] = job;
   std::atomic_thread_fence(std::memory_order_release);
