@@ -448,7 +448,11 @@ def rooflines(res):
         score["frac_by_recorded_trace"] = r4(256.0 * w.N * w.P / trace_us / 1e3 / HBM_PEAK_GBS)
     attn = {"bound": "hbm", "kernel": "qsac_attn_kernel", "achieved": r4(h["attn_GBps"]), "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": r4(h["attn_GBps"] / HBM_PEAK_GBS), "bytes_per_launch": r4(h["attn_bytes"]),
-            "us_per_launch": r4(h["attn_us"]), "timed_by": "HIP events"}
+            "us_per_launch": r4(h["attn_us"]), "timed_by": "HIP events",
+            # the kernel also carries the miss fill: every fetched row is written into its slot (512 B per row)
+            "fill_bytes_written_per_launch": r4(512.0 * res["rows_filled_per_step"]),
+            "frac_counting_fill_writes": r4((h["attn_bytes"] + 512.0 * res["rows_filled_per_step"]) / h["attn_us"] / 1e3
+                                            / HBM_PEAK_GBS)}
     out["score"], out["attn"] = score, attn
     if "pcie" in res:
         p = res["pcie"]
