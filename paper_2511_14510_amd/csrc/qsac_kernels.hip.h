@@ -35,7 +35,12 @@ constexpr int kD = 128;            // head_dim
 constexpr int kRowU4 = 16;         // 16-byte chunks per 256-byte row
 constexpr int kBins = 2048;        // bins per radix level (level 2 uses the first 1024)
 constexpr int kHistCopies = 4;     // one-workgroup select: lane l counts into copy l % 4 (fewer same-address conflicts)
+constexpr int kCandBins = 4096;    // one-workgroup select, guided path: bins of the candidates' first level,
+constexpr int kCandShift = 13;     // each 2^kCandShift keys wide; the second level has 2^kCandShift bins
 constexpr int kHistPitch = kBins + 16;  // words between copies: the same bin of different copies sits in different banks
+static_assert(kCandBins <= kHistCopies * kHistPitch && (1 << kCandShift) <= kHistCopies * kHistPitch &&
+                  kCandBins <= 8 * 1024 && (1 << kCandShift) <= 8 * 1024,
+              "both candidate levels use the one-workgroup select's histogram, 8 bins a thread at most");
 constexpr int kScoreRowsSmall = 256;   // keys per workgroup of the scoring kernel (small-N path)
 constexpr int kScoreRowsLarge = 1024;  // ... when the level-0 histogram is fused in (large-N path)
 constexpr int kSmallMaxN = 65536;      // largest N the one-workgroup select takes: its keys fit in the registers of 1024 threads
@@ -188,24 +193,37 @@ __device__ __forceinline__ double wave_sum_f64_lane63(double v) {
   return v;
 }
 
+// Sum of v over lanes 0..15 of the wave, returned as a wave-uniform value (Kogge-Stone over DPP row 0, then
+// a read of lane 15).  All 64 lanes must be active.
+__device__ __forceinline__ int row0_total(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
+  return __builtin_amdgcn_readlane(v, 15);
+}
+
+// The per-wave values of a workgroup of NW <= 16 wavefronts sit in s[0..NW): returns the sum of the values of
+// the waves below this one; *total gets the sum of all.  Lane l reads s[l] and the sums are taken across lanes.
+template <int NW>
+__device__ __forceinline__ int below_and_total(const int* s, int* total) {
+  static_assert(NW <= 16, "one DPP row holds the per-wave values");
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = lane < NW ? s[lane] : 0;
+  if (total) *total = row0_total(t);
+  return row0_total(lane < wave ? t : 0);
+}
+
 // Exclusive prefix sum of one int per thread over a workgroup of NW wavefronts; *total gets the sum.
 // Contains barriers: every thread of the workgroup must call it.
 template <int NW>
-__device__ __forceinline__ int block_exclusive_scan(int v, int* s_wave /*[NW+1]*/, int* total) {
+__device__ __forceinline__ int block_exclusive_scan(int v, int* s_wave /*[NW]*/, int* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int inc = wave_inclusive_scan(v);
   __syncthreads();  // s_wave may still be read from a previous call
   if (lane == 63) s_wave[wave] = inc;
   __syncthreads();
-  int base = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) {
-    int t = s_wave[w];
-    if (w < wave) base += t;
-    tot += t;
-  }
-  *total = tot;
-  return base + inc - v;
+  return below_and_total<NW>(s_wave, total) + inc - v;
 }
 
 // Exclusive prefix over the waves of a workgroup of one value per wave (the same in all its lanes).
@@ -216,15 +234,7 @@ __device__ __forceinline__ int wave_totals_exclusive(int wave_value, int* s_wave
   __syncthreads();
   if (lane == 0) s_wave[wave] = wave_value;
   __syncthreads();
-  int base = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) {
-    int t = s_wave[w];
-    if (w < wave) base += t;
-    tot += t;
-  }
-  *total = tot;
-  return base;
+  return below_and_total<NW>(s_wave, total);
 }
 
 // The same for two values per wave at once.
@@ -238,24 +248,36 @@ __device__ __forceinline__ void wave_totals_exclusive2(int va, int vb, int* s_wa
     s_wave2[NW + wave] = vb;
   }
   __syncthreads();
-  int ba = 0, bb = 0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) {
-    if (w < wave) {
-      ba += s_wave2[w];
-      bb += s_wave2[NW + w];
-    }
+  *base_a = below_and_total<NW>(s_wave2, nullptr);
+  *base_b = below_and_total<NW>(s_wave2 + NW, nullptr);
+}
+
+// The same for three values per wave at once; *total_c gets the sum of the third.
+template <int NW>
+__device__ __forceinline__ void wave_totals_exclusive3(int va, int vb, int vc, int* s_wave3 /*[3*NW]*/, int* base_a,
+                                                       int* base_b, int* base_c, int* total_c) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) {
+    s_wave3[wave] = va;
+    s_wave3[NW + wave] = vb;
+    s_wave3[2 * NW + wave] = vc;
   }
-  *base_a = ba;
-  *base_b = bb;
+  __syncthreads();
+  *base_a = below_and_total<NW>(s_wave3, nullptr);
+  *base_b = below_and_total<NW>(s_wave3 + NW, nullptr);
+  *base_c = below_and_total<NW>(s_wave3 + 2 * NW, total_c);
 }
 
 // Among bins [0, nbins) of `hist`, finds the bin b with  count(bins > b) < need <= count(bins >= b).
-// Returns b; *above = count(bins > b).  NT threads (nbins is a multiple of NT, at most 8 bins per
-// thread); the histogram may be split over COPIES copies kHistPitch words apart; contains barriers.
+// Returns b and *above = count(bins > b), or -1 if the bins hold fewer than `need` in all; *total (optional)
+// gets the sum of all bins, *in_bin (optional; s_res then has three words) the count of bin b.  NT threads (nbins is a multiple of NT, at most 8 bins per thread); the histogram
+// may be split over COPIES copies kHistPitch words apart.  Contains two barriers; the caller's barrier that
+// publishes the histogram must also be the last thing before the call that touched s_wave and s_res.
 template <int NT, int COPIES = 1>
 __device__ __forceinline__ int find_bin(const u32* hist, int nbins, int need, int* above, int* s_wave,
-                                        int* s_res) {
+                                        int* s_res, int* total = nullptr, int* in_bin = nullptr) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int per = nbins / NT;
   // thread t owns bins [hi - per + 1, hi] counted from the top: t = 0 owns the highest bins
   const int hi = nbins - 1 - (int)threadIdx.x * per;
@@ -270,12 +292,12 @@ __device__ __forceinline__ int find_bin(const u32* hist, int nbins, int need, in
     }
     local += c[i];
   }
-  if (threadIdx.x == 0) {
-    s_res[0] = 0;
-    s_res[1] = 0;
-  }
+  const int inc = wave_inclusive_scan(local);
+  if (lane == 63) s_wave[wave] = inc;
+  __syncthreads();
   int tot;
-  int before = block_exclusive_scan<NT / 64>(local, s_wave, &tot);  // keys in bins above this thread's
+  const int before = below_and_total<NT / 64>(s_wave, &tot) + inc - local;  // keys in bins above this thread's
+  if (total) *total = tot;
   if (before < need && need <= before + local) {
     int run = before;
 #pragma unroll
@@ -284,16 +306,17 @@ __device__ __forceinline__ int find_bin(const u32* hist, int nbins, int need, in
         if (run < need && need <= run + c[i]) {
           s_res[0] = hi - i;
           s_res[1] = run;
+          if (in_bin) s_res[2] = c[i];
         }
         run += c[i];
       }
     }
   }
   __syncthreads();
-  int b = s_res[0];
+  if (need > tot) return -1;
   *above = s_res[1];
-  __syncthreads();
-  return b;
+  if (in_bin) *in_bin = s_res[2];
+  return s_res[0];
 }
 
 // ---------------------------------------------------------------- gate
@@ -874,9 +897,20 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_list_kernel(
 //     WPL bounds the words a lane holds: words <= 64 * WPL * NT / 64)
 //  B. bitmap of the tokens cached before the step (from slot_idx);
 //  C. ascending index list, hit mask, ascending list of tokens to fetch;
-//  D. ascending list of slots whose token left the set;
+//  D. ascending list of slots whose token left the set (its counts travel with C's through one exchange);
 //  E. the i-th such slot takes the i-th token to fetch (slot table and fetch_tok).
-template <int NT, int WPL>
+// STAGE: the caller gives room in LDS (DiffStage: k ints each for ms, mt and tk, k bytes for hm).  The four
+// lists are built there and leave with coalesced stores, and E takes the miss lists from there (scattered 4-byte
+// stores from every lane are what the emission otherwise waits on).
+// skip_ties: the caller has already put every key equal to the k-th key into nw (r and eq are not read).
+struct DiffStage {
+  int* ms = nullptr;
+  int* mt = nullptr;
+  int* tk = nullptr;
+  uint8_t* hm = nullptr;
+};
+
+template <int NT, int WPL, bool STAGE = false>
 __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __restrict__ eq,
                                             u32* __restrict__ old, bool was_valid, int r, int words,
                                             int k, int* __restrict__ sl, int* __restrict__ ss,
@@ -884,7 +918,8 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
                                             int* __restrict__ mt, int* __restrict__ ft,
                                             int* __restrict__ miss_count_p, u32* __restrict__ valid_p,
                                             u64* __restrict__ stats, bool resident, int host_row_bytes,
-                                            int* s_wave) {
+                                            int* s_wave /*[3 * NT / 64]*/, DiffStage st = DiffStage(),
+                                            bool skip_ties = false) {
   constexpr int NW = NT / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // Wave w owns the contiguous words [wb, we); lane l takes words wb + l, wb + l + 64, ... (at most
@@ -905,43 +940,45 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
       if (j0 + i < j1) mytok[i] = sl[j0 + i];
   }
   for (int j = tid; j < k; j += NT) ft[j] = -1;  // slots that keep their row; E names the others
-  int total;
   // A
-  u32 ev[WPL];
-  int ceq = 0;
-#pragma unroll
-  for (int u = 0; u < WPL; ++u) {
-    const int w = wb + u * 64 + lane;
-    ev[u] = (u < rounds && w < we) ? eq[w] : 0u;
-    ceq += __popc(ev[u]);
-  }
-  ceq = __shfl(wave_inclusive_scan(ceq), 63);
-  int run = wave_totals_exclusive<NW>(ceq, s_wave, &total);
-  if (total == r) {  // every key equal to the k-th key belongs to the set (the usual case: it is alone)
-#pragma unroll
-    for (int u = 0; u < WPL; ++u)
-      if (ev[u]) nw[wb + u * 64 + lane] |= ev[u];
-  } else {
+  if (!skip_ties) {
+    u32 ev[WPL];
+    int ceq = 0;
 #pragma unroll
     for (int u = 0; u < WPL; ++u) {
-      if (u < rounds) {  // uniform: every lane takes part in the scan
-        u32 e = ev[u];
-        const int c = __popc(e);
-        const int inc = wave_inclusive_scan(c);
-        const int rank = run + inc - c;  // keys equal to the k-th key at lower indices
-        if (c && rank + c > r) {         // keep only the lowest (r - rank) bits of e
-          int keep = r - rank;
-          u32 kept = 0;
-          while (keep > 0 && e) {
-            u32 low = e & (0u - e);
-            kept |= low;
-            e ^= low;
-            --keep;
+      const int w = wb + u * 64 + lane;
+      ev[u] = (u < rounds && w < we) ? eq[w] : 0u;
+      ceq += __popc(ev[u]);
+    }
+    ceq = __shfl(wave_inclusive_scan(ceq), 63);
+    int total;
+    int run = wave_totals_exclusive<NW>(ceq, s_wave, &total);
+    if (total == r) {  // every key equal to the k-th key belongs to the set (the usual case: it is alone)
+#pragma unroll
+      for (int u = 0; u < WPL; ++u)
+        if (ev[u]) nw[wb + u * 64 + lane] |= ev[u];
+    } else {
+#pragma unroll
+      for (int u = 0; u < WPL; ++u) {
+        if (u < rounds) {  // uniform: every lane takes part in the scan
+          u32 e = ev[u];
+          const int c = __popc(e);
+          const int inc = wave_inclusive_scan(c);
+          const int rank = run + inc - c;  // keys equal to the k-th key at lower indices
+          if (c && rank + c > r) {         // keep only the lowest (r - rank) bits of e
+            int keep = r - rank;
+            u32 kept = 0;
+            while (keep > 0 && e) {
+              u32 low = e & (0u - e);
+              kept |= low;
+              e ^= low;
+              --keep;
+            }
+            e = kept;
           }
-          e = kept;
+          if (e) nw[wb + u * 64 + lane] |= e;
+          run += __shfl(inc, 63);
         }
-        if (e) nw[wb + u * 64 + lane] |= e;
-        run += __shfl(inc, 63);
       }
     }
   }
@@ -959,7 +996,7 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
     }
   }
   __syncthreads();
-  // C
+  // C and D share one exchange of wave totals
   u32 av[WPL], ov[WPL];
   int cn = 0, cm = 0;
 #pragma unroll
@@ -971,40 +1008,7 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
     cn += __popc(av[u]);
     cm += __popc(av[u] & ~ov[u]);
   }
-  cn = __shfl(wave_inclusive_scan(cn), 63);
-  cm = __shfl(wave_inclusive_scan(cm), 63);
-  int runn, runm;
-  wave_totals_exclusive2<NW>(cn, cm, s_wave, &runn, &runm);
-#pragma unroll
-  for (int u = 0; u < WPL; ++u) {
-    if (u < rounds) {
-      u32 a = av[u];
-      const u32 o = ov[u];
-      const int c1 = __popc(a), c2 = __popc(a & ~o);
-      const int i1 = wave_inclusive_scan(c1), i2 = wave_inclusive_scan(c2);
-      int jn = runn + i1 - c1, jm = runm + i2 - c2;
-      const int w = wb + u * 64 + lane;
-      while (a) {
-        const int bit = __ffs(a) - 1;
-        a &= a - 1;
-        const int tok = w * 32 + bit;
-        const bool hit = (o >> bit) & 1u;
-        if (jn < k) {  // the set has exactly k members; the guard only protects the buffers
-          tk[jn] = tok;
-          ss[jn] = tok;
-          hm[jn] = (uint8_t)hit;
-        }
-        ++jn;
-        if (!hit) {
-          if (jm < k) mt[jm] = tok;
-          ++jm;
-        }
-      }
-      runn += __shfl(i1, 63);
-      runm += __shfl(i2, 63);
-    }
-  }
-  // D
+  // D, counting: this thread's slots whose token left the set (all of them if the cache was invalid)
   bool evict[4] = {false, false, false, false};
   int ce = 0;
   if (slots_in_regs) {
@@ -1024,12 +1028,55 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
       ce += e;
     }
   }
-  int je = block_exclusive_scan<NT / 64>(ce, s_wave, &total);
-  const int m = total;
+  cn = __shfl(wave_inclusive_scan(cn), 63);
+  cm = __shfl(wave_inclusive_scan(cm), 63);
+  const int inc_e = wave_inclusive_scan(ce);
+  int runn, runm, rune, m;
+  wave_totals_exclusive3<NW>(cn, cm, __shfl(inc_e, 63), s_wave, &runn, &runm, &rune, &m);
+  // C, emission
+#pragma unroll
+  for (int u = 0; u < WPL; ++u) {
+    if (u < rounds) {
+      u32 a = av[u];
+      const u32 o = ov[u];
+      const int c1 = __popc(a), c2 = __popc(a & ~o);
+      const int i1 = wave_inclusive_scan(c1), i2 = wave_inclusive_scan(c2);
+      int jn = runn + i1 - c1, jm = runm + i2 - c2;
+      const int w = wb + u * 64 + lane;
+      while (a) {
+        const int bit = __ffs(a) - 1;
+        a &= a - 1;
+        const int tok = w * 32 + bit;
+        const bool hit = (o >> bit) & 1u;
+        if (jn < k) {  // the set has exactly k members; the guard only protects the buffers
+          if (STAGE) {
+            st.tk[jn] = tok;
+            st.hm[jn] = (uint8_t)hit;
+          } else {
+            tk[jn] = tok;
+            ss[jn] = tok;
+            hm[jn] = (uint8_t)hit;
+          }
+        }
+        ++jn;
+        if (!hit) {
+          if (jm < k) (STAGE ? st.mt : mt)[jm] = tok;
+          ++jm;
+        }
+      }
+      runn += __shfl(i1, 63);
+      runm += __shfl(i2, 63);
+    }
+  }
+  // D, emission
+  int je = rune + inc_e - ce;
   if (slots_in_regs) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      if (evict[i]) ms[je++] = j0 + i;
+      if (evict[i]) {
+        (STAGE ? st.ms : ms)[je] = j0 + i;
+        ++je;
+      }
   } else {
     for (int j = j0; j < j1; ++j) {
       bool e = true;
@@ -1037,15 +1084,30 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
         const int tok = sl[j];
         e = !((nw[tok >> 5] >> (tok & 31)) & 1u);
       }
-      if (e) ms[je++] = j;
+      if (e) {
+        (STAGE ? st.ms : ms)[je] = j;
+        ++je;
+      }
     }
   }
   __syncthreads();
+  if (STAGE) {
+    for (int i = tid; i < k; i += NT) {
+      const int tok = st.tk[i];
+      tk[i] = tok;
+      ss[i] = tok;
+      hm[i] = st.hm[i];
+    }
+  }
   // E
   for (int i = tid; i < m; i += NT) {
-    const int slot = ms[i], tok = mt[i];
+    const int slot = (STAGE ? st.ms : ms)[i], tok = (STAGE ? st.mt : mt)[i];
     sl[slot] = tok;
     ft[slot] = tok;
+    if (STAGE) {
+      ms[i] = slot;
+      mt[i] = tok;
+    }
   }
   if (tid == 0) {
     *miss_count_p = m;
@@ -1074,7 +1136,7 @@ __global__ __launch_bounds__(kDiffThreads) void qsac_diff_kernel(
     report_cached_set(set_sorted, topk_idx, hit_mask, p, k, k_max);
     return;
   }
-  __shared__ int s_wave[32];
+  __shared__ int s_wave[64];
   diff_phases<kDiffThreads, WPL>(bm_new + (size_t)p * words, bm_eq + (size_t)p * words, bm_old + (size_t)p * words,
                             valid[p] != 0, sel_r[(size_t)p * kSelStride], words, k, slot_idx + (size_t)p * k_max,
                             set_sorted + (size_t)p * k_max, topk_idx + (size_t)p * k, hit_mask + (size_t)p * k,
@@ -1120,24 +1182,32 @@ struct SelArgs {
 // sample's r_sample-th largest key.  r_sample is chosen so that the number of keys >= g falls
 // between k and list_cap with near certainty.  k <= #{key >= g} proves T >= g, i.e. every key of
 // the top-k, and every key equal to T, is among those candidates: they are compacted into an
-// LDS list (a few per thread) and the three radix levels and the bitmaps run over the list
-// only.  If the count falls outside [k, list_cap] the full path runs; the result is the same
-// either way.
+// LDS list (a few per thread) and T is pinned over the list only, by two histogram levels of
+// d = key - g (the candidates share their leading key bits, so digits of the key itself would
+// pile them into a handful of bins): d >> kCandShift, counted while the list is built, then the
+// low kCandShift bits within that level's bin.  If the count falls outside [k, list_cap] the
+// full path runs, and if T lies too far above g for the first level the three plain levels run
+// over the list; the result is the same every way.  When every key equal to T belongs to the
+// set (nearly always: T is alone) the bitmap pass puts them into the set directly and the diff
+// skips its tie phase.
 //
-// Dynamic LDS (s_dyn): three bitmaps of bm_words words, then list_cap keys and list_cap indices.
+// Dynamic LDS (s_dyn): three bitmaps of bm_words words, then list_cap (key, index) entries of 8 bytes (the diff's
+// staging lists take that room over once T is known).
 template <int VPT, int NT>
 __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSrc& src, int p, u32* s_dyn) {
   constexpr int NV = VPT;
   __shared__ u32 s_hist[kHistCopies * kHistPitch];
-  __shared__ int s_wave[32];
-  __shared__ int s_res[2];
+  __shared__ int s_wave[64];
+  __shared__ int s_res[3];
+  __shared__ u32 s_small[64];
+  __shared__ int s_flag[2];  // [0] a wave ran out of list room, [1] keys gathered in s_small
+  constexpr int NW = NT / 64;
   const int bm_words = A.bm_words, k = A.k, k_max = A.k_max;
   u32* s_new = s_dyn;
   u32* s_eq = s_dyn + bm_words;
   u32* s_old = s_dyn + 2 * bm_words;
-  u32* l_key = s_dyn + 3 * bm_words;
-  int* l_idx = reinterpret_cast<int*>(l_key + A.list_cap);
-  const int tid = threadIdx.x;
+  u64* l_ent = reinterpret_cast<u64*>(s_dyn + 3 * bm_words);  // bm_words is even: 8-byte aligned
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const v4u* kp4 = reinterpret_cast<const v4u*>(A.keys + (size_t)p * A.n_pad);
   const int n = (int)A.N;
   const int nvec = (n + 3) >> 2;  // n_pad is a multiple of 8192, so whole vectors can be read
@@ -1162,11 +1232,12 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
   auto level_sub = [](int level) { return level == 0 ? 21 : (level == 1 ? 10 : 0); };
   auto level_mask = [](int level) { return level == 2 ? 0x3ffu : 0x7ffu; };
 
-  bool guided = false;  // uniform over the workgroup
-  int n_cand = 0, off = 0;
+  bool guided = false;    // uniform over the workgroup
+  bool all_ties = false;  // uniform: every key equal to the k-th key belongs to the set and is already in s_new
   u32 bound = 0;
   if (A.r_sample > 0) {
     for (int i = tid; i < 4096; i += NT) s_hist[i] = 0;
+    if (tid < 2) s_flag[tid] = 0;
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -1175,54 +1246,99 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
     }
     __syncthreads();
     bound = (u32)find_bin<NT, 1>(s_hist, 4096, A.r_sample, &above, s_wave, s_res) << 20;
+    // cleared for the candidates' first level (the barrier after the compaction publishes it)
+    for (int i = tid; i < kCandBins; i += NT) s_hist[i] = 0;
   }
   if (bound != 0u) {
-    int cnt = 0;
-#pragma unroll
-    for (int i = 0; i < NV; ++i)
-      cnt += (int)(kreg[i].x >= bound) + (int)(kreg[i].y >= bound) + (int)(kreg[i].z >= bound) +
-             (int)(kreg[i].w >= bound);
-    off = block_exclusive_scan<NT / 64>(cnt, s_wave, &n_cand);
-    guided = n_cand >= k && n_cand <= A.list_cap;
-  }
-  if (guided) {
-    // candidates into the list (its order is irrelevant: histograms and bitmaps do not depend on it)
+    // Candidates (key >= bound) into the list as (key, index) entries.  The order of the list is irrelevant
+    // (histograms and bitmaps do not depend on it): every wave appends to its own part of the list, each key slot
+    // by ballot rank, and is the only reader of that part afterwards, so no count has to be exchanged first.  The
+    // last entry of a part only catches what does not fit; a wave that gets that far calls the guided path off.
+    const int part = A.list_cap / NW;
+    u64* my_ent = l_ent + wave * part;
+    int n_mine = 0;  // wave-uniform
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const u32 ks[4] = {kreg[i].x, kreg[i].y, kreg[i].z, kreg[i].w};
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (ks[j] >= bound) {
-          l_key[off] = ks[j];
-          l_idx[off] = 4 * (tid + i * NT) + j;
-          ++off;
+      for (int j = 0; j < 4; ++j) {
+        const bool c = ks[j] >= bound;
+        const u64 m = __ballot(c);
+        if (c) {
+          const int pos = (int)__builtin_amdgcn_mbcnt_hi((u32)(m >> 32), __builtin_amdgcn_mbcnt_lo((u32)m, (u32)n_mine));
+          my_ent[min(pos, part - 1)] = ((u64)ks[j] << 32) | (u32)(4 * (tid + i * NT) + j);
         }
+        n_mine += __popcll(m);
+      }
+    }
+    if (n_mine > part - 1) {
+      n_mine = 0;
+      if (lane == 0) s_flag[0] = 1;
     }
     for (int i = tid; i < 2 * bm_words; i += NT) s_new[i] = 0;  // s_new and s_eq are adjacent
+    __syncthreads();
+    // All candidates share the leading key bits, so the radix digit is taken from d = key - bound: d >> kCandShift
+    // in kCandBins bins (the last bin also takes everything further up).
+    for (int e = lane; e < n_mine; e += 64)
+      atomicAdd(&s_hist[min(((u32)(my_ent[e] >> 32) - bound) >> kCandShift, (u32)kCandBins - 1u)], 1u);
+    __syncthreads();
+    int in_bin;
+    const int b1 = find_bin<NT, 1>(s_hist, kCandBins, k, &above, s_wave, s_res, nullptr, &in_bin);
+    // b1 >= 0: at least k candidates, which proves that the k-th key is among them
+    guided = b1 >= 0 && s_flag[0] == 0;
+    if (guided) {
+      if (b1 != kCandBins - 1 && in_bin <= 64) {
+        // The k-th key is one of the few keys of bin b1: they are gathered and every wave ranks them by itself.
+        need -= above;
+        for (int e = lane; e < n_mine; e += 64) {
+          const u32 key = (u32)(my_ent[e] >> 32);
+          if (((key - bound) >> kCandShift) == (u32)b1) s_small[atomicAdd(&s_flag[1], 1)] = key;
+        }
+        __syncthreads();
+        const int n_small = __builtin_amdgcn_readfirstlane(in_bin);
+        const u32 v = lane < n_small ? s_small[lane] : 0u;
+        int gt = 0, eq = 0;  // keys of the bin above / equal to this lane's (itself included)
+        for (int j = 0; j < n_small; ++j) {
+          const u32 x = (u32)__builtin_amdgcn_readlane((int)v, j);
+          gt += (int)(x > v);
+          eq += (int)(x == v);
+        }
+        const u64 holds = __ballot(lane < n_small && gt < need && need <= gt + eq);
+        const int from = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)holds) - 1);
+        prefix = (u32)__builtin_amdgcn_readlane((int)v, from);
+        need -= __builtin_amdgcn_readlane(gt, from);
+        all_ties = need == __builtin_amdgcn_readlane(eq, from);
+      } else {
+        // too many keys share that bin, or the k-th key lies further above the bound than the bins resolve: the
+        // plain three levels over the list
 #pragma unroll
-    for (int level = 0; level < 3; ++level) {
-      for (int i = tid; i < kBins; i += NT) s_hist[i] = 0;
-      __syncthreads();
-      for (int e = tid; e < n_cand; e += NT) {
-        const u32 key = l_key[e];
-        if (level == 0 || (key >> level_shift(level)) == prefix)
-          atomicAdd(&s_hist[(key >> level_sub(level)) & level_mask(level)], 1u);
+        for (int level = 0; level < 3; ++level) {
+          for (int i = tid; i < kBins; i += NT) s_hist[i] = 0;
+          __syncthreads();
+          for (int e = lane; e < n_mine; e += 64) {
+            const u32 key = (u32)(my_ent[e] >> 32);
+            if (level == 0 || (key >> level_shift(level)) == prefix)
+              atomicAdd(&s_hist[(key >> level_sub(level)) & level_mask(level)], 1u);
+          }
+          __syncthreads();
+          const u32 bsel = (u32)find_bin<NT, 1>(s_hist, level == 2 ? 1024 : kBins, need, &above, s_wave, s_res);
+          need -= above;
+          prefix = level == 0 ? bsel : (prefix << (level == 1 ? 11 : 10)) | bsel;
+        }
       }
-      __syncthreads();
-      const u32 bsel = (u32)find_bin<NT, 1>(s_hist, level == 2 ? 1024 : kBins, need, &above, s_wave, s_res);
-      need -= above;
-      prefix = level == 0 ? bsel : (prefix << (level == 1 ? 11 : 10)) | bsel;
+      const u32 T = prefix;
+      for (int e = lane; e < n_mine; e += 64) {
+        const u64 ent = my_ent[e];
+        const u32 key = (u32)(ent >> 32);
+        const int idx = (int)(u32)ent;
+        if (key > T || (all_ties && key == T))
+          atomicOr(&s_new[idx >> 5], 1u << (idx & 31));
+        else if (key == T)
+          atomicOr(&s_eq[idx >> 5], 1u << (idx & 31));
+      }
     }
-    const u32 T = prefix;
-    for (int e = tid; e < n_cand; e += NT) {
-      const u32 key = l_key[e];
-      const int idx = l_idx[e];
-      if (key > T)
-        atomicOr(&s_new[idx >> 5], 1u << (idx & 31));
-      else if (key == T)
-        atomicOr(&s_eq[idx >> 5], 1u << (idx & 31));
-    }
-  } else {
+  }
+  if (!guided) {
     u32* my_hist = s_hist + (tid & (kHistCopies - 1)) * kHistPitch;
 #pragma unroll
     for (int level = 0; level < 3; ++level) {
@@ -1266,12 +1382,25 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
   // prefix: the k-th largest key; `need` of the keys equal to it belong to the set
   if (tid == 0 && guided) atomicAdd(&A.stats[6], 1ull);
   __syncthreads();
-  // 65536 keys = 2048 bitmap words
-  diff_phases<NT, 2048 / NT>(s_new, s_eq, s_old, A.valid[p] != 0, need, words, k, A.slot_idx + (size_t)p * k_max,
-                             A.set_sorted + (size_t)p * k_max, A.topk_idx + (size_t)p * k, A.hit_mask + (size_t)p * k,
-                             A.miss_slot + (size_t)p * k_max, A.miss_tok + (size_t)p * k_max,
-                             A.fetch_tok + (size_t)p * k_max, A.miss_count + p, A.valid + p, A.stats,
-                             src.slot[p % A.Hkv] >= 0, src.host_row_bytes, s_wave);
+  // 65536 keys = 2048 bitmap words.  The candidate list is dead by now: its room stages the diff's lists if
+  // they fit.
+#define QSAC_DIFF_ARGS                                                                                              \
+  s_new, s_eq, s_old, A.valid[p] != 0, need, words, k, A.slot_idx + (size_t)p * k_max,                              \
+      A.set_sorted + (size_t)p * k_max, A.topk_idx + (size_t)p * k, A.hit_mask + (size_t)p * k,                      \
+      A.miss_slot + (size_t)p * k_max, A.miss_tok + (size_t)p * k_max, A.fetch_tok + (size_t)p * k_max,              \
+      A.miss_count + p, A.valid + p, A.stats, src.slot[p % A.Hkv] >= 0, src.host_row_bytes, s_wave
+  if (3 * k + (k + 3) / 4 <= 2 * A.list_cap) {
+    int* const room = reinterpret_cast<int*>(l_ent);
+    DiffStage st;
+    st.ms = room;
+    st.mt = room + k;
+    st.tk = room + 2 * k;
+    st.hm = reinterpret_cast<uint8_t*>(room + 3 * k);
+    diff_phases<NT, 2048 / NT, true>(QSAC_DIFF_ARGS, st, all_ties);
+  } else {
+    diff_phases<NT, 2048 / NT, false>(QSAC_DIFF_ARGS, DiffStage(), all_ties);
+  }
+#undef QSAC_DIFF_ARGS
 }
 
 template <int VPT, int NT>
@@ -1358,12 +1487,13 @@ __global__ __launch_bounds__(256) void qsac_publish_kernel(const int* __restrict
     h_tok[i] = mt[i];
   }
   if (threadIdx.x == 0) h_count[p] = m;
-  // every store of this workgroup has been acknowledged by the memory system before it counts itself done
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __builtin_amdgcn_s_waitcnt(0);
+  // Every workgroup releases its own stores to the host before it counts itself done: workgroups run on
+  // different XCDs, host memory is cached in each XCD's L2, and the release that goes with Flag1 below writes
+  // back only the L2 of the one workgroup that executes it.
+  __threadfence_system();
   __syncthreads();
   if (threadIdx.x == 0) {
-    const u32 done = atomicAdd(&state[1], 1u);
+    const u32 done = __hip_atomic_fetch_add(&state[1], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
     if (done == (u32)P - 1) {
       state[1] = 0;
       const u32 seq = state[0] + 1;
