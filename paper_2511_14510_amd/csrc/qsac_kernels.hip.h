@@ -35,12 +35,11 @@ constexpr int kD = 128;            // head_dim
 constexpr int kRowU4 = 16;         // 16-byte chunks per 256-byte row
 constexpr int kBins = 2048;        // bins per radix level (level 2 uses the first 1024)
 constexpr int kHistCopies = 4;     // one-workgroup select: lane l counts into copy l % 4 (fewer same-address conflicts)
-constexpr int kCandBins = 4096;    // one-workgroup select, guided path: bins of the candidates' first level,
-constexpr int kCandShift = 13;     // each 2^kCandShift keys wide; the second level has 2^kCandShift bins
+constexpr int kCandBins = 4096;    // one-workgroup select, guided path: bins of the candidates' histogram,
+constexpr int kCandShift = 13;     // each 2^kCandShift keys wide
 constexpr int kHistPitch = kBins + 16;  // words between copies: the same bin of different copies sits in different banks
-static_assert(kCandBins <= kHistCopies * kHistPitch && (1 << kCandShift) <= kHistCopies * kHistPitch &&
-                  kCandBins <= 8 * 1024 && (1 << kCandShift) <= 8 * 1024,
-              "both candidate levels use the one-workgroup select's histogram, 8 bins a thread at most");
+static_assert(4096 + kCandBins <= kHistCopies * kHistPitch && kCandBins <= 8 * 1024,
+              "the candidates' level sits behind the sample's 4096 bins in the one-workgroup select's histogram");
 constexpr int kScoreRowsSmall = 256;   // keys per workgroup of the scoring kernel (small-N path)
 constexpr int kScoreRowsLarge = 1024;  // ... when the level-0 histogram is fused in (large-N path)
 constexpr int kSmallMaxN = 65536;      // largest N the one-workgroup select takes: its keys fit in the registers of 1024 threads
@@ -193,6 +192,15 @@ __device__ __forceinline__ double wave_sum_f64_lane63(double v) {
   return v;
 }
 
+// Clears `words` 32-bit words of LDS at p (16-byte aligned) with 16-byte stores; NT threads.
+template <int NT>
+__device__ __forceinline__ void lds_zero(u32* p, int words) {
+  v4u* p4 = reinterpret_cast<v4u*>(p);
+  const int n4 = words >> 2;
+  for (int i = threadIdx.x; i < n4; i += NT) p4[i] = v4u{0, 0, 0, 0};
+  if ((int)threadIdx.x < (words & 3)) p[(n4 << 2) + threadIdx.x] = 0;
+}
+
 // Sum of v over lanes 0..15 of the wave, returned as a wave-uniform value (Kogge-Stone over DPP row 0, then
 // a read of lane 15).  All 64 lanes must be active.
 __device__ __forceinline__ int row0_total(int v) {
@@ -253,11 +261,12 @@ __device__ __forceinline__ void wave_totals_exclusive2(int va, int vb, int* s_wa
 }
 
 // The same for three values per wave at once; *total_c gets the sum of the third.
-template <int NW>
+// LEAD = false: a barrier already separates the call from the last use of s_wave3.
+template <int NW, bool LEAD = true>
 __device__ __forceinline__ void wave_totals_exclusive3(int va, int vb, int vc, int* s_wave3 /*[3*NW]*/, int* base_a,
                                                        int* base_b, int* base_c, int* total_c) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  __syncthreads();
+  if (LEAD) __syncthreads();
   if (lane == 0) {
     s_wave3[wave] = va;
     s_wave3[NW + wave] = vb;
@@ -272,7 +281,7 @@ __device__ __forceinline__ void wave_totals_exclusive3(int va, int vb, int vc, i
 // Among bins [0, nbins) of `hist`, finds the bin b with  count(bins > b) < need <= count(bins >= b).
 // Returns b and *above = count(bins > b), or -1 if the bins hold fewer than `need` in all; *total (optional)
 // gets the sum of all bins, *in_bin (optional; s_res then has three words) the count of bin b.  NT threads (nbins is a multiple of NT, at most 8 bins per thread); the histogram
-// may be split over COPIES copies kHistPitch words apart.  Contains two barriers; the caller's barrier that
+// (16-byte aligned) may be split over COPIES copies kHistPitch words apart.  Contains two barriers; the caller's barrier that
 // publishes the histogram must also be the last thing before the call that touched s_wave and s_res.
 template <int NT, int COPIES = 1>
 __device__ __forceinline__ int find_bin(const u32* hist, int nbins, int need, int* above, int* s_wave,
@@ -283,14 +292,21 @@ __device__ __forceinline__ int find_bin(const u32* hist, int nbins, int need, in
   const int hi = nbins - 1 - (int)threadIdx.x * per;
   int c[8];
   int local = 0;
+  if (COPIES == 1 && per == 4) {  // hist is 16-byte aligned: the four bins in one read
+    const v4u q = *reinterpret_cast<const v4u*>(hist + hi - 3);
+    c[0] = (int)q.w, c[1] = (int)q.z, c[2] = (int)q.y, c[3] = (int)q.x;
+    c[4] = c[5] = c[6] = c[7] = 0;
+    local = c[0] + c[1] + c[2] + c[3];
+  } else {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    c[i] = 0;
-    if (i < per) {
+    for (int i = 0; i < 8; ++i) {
+      c[i] = 0;
+      if (i < per) {
 #pragma unroll
-      for (int cp = 0; cp < COPIES; ++cp) c[i] += (int)hist[cp * kHistPitch + hi - i];
+        for (int cp = 0; cp < COPIES; ++cp) c[i] += (int)hist[cp * kHistPitch + hi - i];
+      }
+      local += c[i];
     }
-    local += c[i];
   }
   const int inc = wave_inclusive_scan(local);
   if (lane == 63) s_wave[wave] = inc;
@@ -910,6 +926,17 @@ struct DiffStage {
   uint8_t* hm = nullptr;
 };
 
+// The slot tokens diff_phases keeps in registers (thread t: slots [t * spt, t * spt + spt) with spt = ceil(k / NT),
+// if spt <= 4), for callers that can request them long before the diff starts.  Reads the slot table whether or
+// not the cache is valid (the table exists either way; B and D ignore what an invalid cache held).
+template <int NT>
+__device__ __forceinline__ void diff_slot_tokens(const int* __restrict__ sl, int k, int tok[4]) {
+  const int spt = (k + NT - 1) / NT;
+  const int j0 = min((int)threadIdx.x * spt, k), j1 = min(j0 + spt, k);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) tok[i] = (spt <= 4 && j0 + i < j1) ? sl[j0 + i] : 0;
+}
+
 template <int NT, int WPL, bool STAGE = false>
 __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __restrict__ eq,
                                             u32* __restrict__ old, bool was_valid, int r, int words,
@@ -919,7 +946,7 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
                                             int* __restrict__ miss_count_p, u32* __restrict__ valid_p,
                                             u64* __restrict__ stats, bool resident, int host_row_bytes,
                                             int* s_wave /*[3 * NT / 64]*/, DiffStage st = DiffStage(),
-                                            bool skip_ties = false) {
+                                            bool skip_ties = false, const int* pre_tok = nullptr) {
   constexpr int NW = NT / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // Wave w owns the contiguous words [wb, we); lane l takes words wb + l, wb + l + 64, ... (at most
@@ -934,7 +961,10 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
   const int j0 = min(tid * spt, k), j1 = min(j0 + spt, k);
   const bool slots_in_regs = spt <= 4;  // uniform
   int mytok[4] = {0, 0, 0, 0};
-  if (was_valid && slots_in_regs) {
+  if (pre_tok) {  // the caller has read them already (diff_slot_tokens)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) mytok[i] = pre_tok[i];
+  } else if (was_valid && slots_in_regs) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       if (j0 + i < j1) mytok[i] = sl[j0 + i];
@@ -950,7 +980,7 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
       ev[u] = (u < rounds && w < we) ? eq[w] : 0u;
       ceq += __popc(ev[u]);
     }
-    ceq = __shfl(wave_inclusive_scan(ceq), 63);
+    ceq = __builtin_amdgcn_readlane(wave_inclusive_scan(ceq), 63);
     int total;
     int run = wave_totals_exclusive<NW>(ceq, s_wave, &total);
     if (total == r) {  // every key equal to the k-th key belongs to the set (the usual case: it is alone)
@@ -977,7 +1007,7 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
             e = kept;
           }
           if (e) nw[wb + u * 64 + lane] |= e;
-          run += __shfl(inc, 63);
+          run += __builtin_amdgcn_readlane(inc, 63);
         }
       }
     }
@@ -1028,11 +1058,11 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
       ce += e;
     }
   }
-  cn = __shfl(wave_inclusive_scan(cn), 63);
-  cm = __shfl(wave_inclusive_scan(cm), 63);
+  cn = __builtin_amdgcn_readlane(wave_inclusive_scan(cn), 63);
+  cm = __builtin_amdgcn_readlane(wave_inclusive_scan(cm), 63);
   const int inc_e = wave_inclusive_scan(ce);
   int runn, runm, rune, m;
-  wave_totals_exclusive3<NW>(cn, cm, __shfl(inc_e, 63), s_wave, &runn, &runm, &rune, &m);
+  wave_totals_exclusive3<NW, false>(cn, cm, __builtin_amdgcn_readlane(inc_e, 63), s_wave, &runn, &runm, &rune, &m);
   // C, emission
 #pragma unroll
   for (int u = 0; u < WPL; ++u) {
@@ -1064,8 +1094,8 @@ __device__ __forceinline__ void diff_phases(u32* __restrict__ nw, const u32* __r
           ++jm;
         }
       }
-      runn += __shfl(i1, 63);
-      runm += __shfl(i2, 63);
+      runn += __builtin_amdgcn_readlane(i1, 63);
+      runm += __builtin_amdgcn_readlane(i2, 63);
     }
   }
   // D, emission
@@ -1182,21 +1212,22 @@ struct SelArgs {
 // sample's r_sample-th largest key.  r_sample is chosen so that the number of keys >= g falls
 // between k and list_cap with near certainty.  k <= #{key >= g} proves T >= g, i.e. every key of
 // the top-k, and every key equal to T, is among those candidates: they are compacted into an
-// LDS list (a few per thread) and T is pinned over the list only, by two histogram levels of
-// d = key - g (the candidates share their leading key bits, so digits of the key itself would
-// pile them into a handful of bins): d >> kCandShift, counted while the list is built, then the
-// low kCandShift bits within that level's bin.  If the count falls outside [k, list_cap] the
-// full path runs, and if T lies too far above g for the first level the three plain levels run
-// over the list; the result is the same every way.  When every key equal to T belongs to the
-// set (nearly always: T is alone) the bitmap pass puts them into the set directly and the diff
-// skips its tie phase.
+// LDS list (each wave appends to its own part of the list, by ballot rank, and stays its only
+// reader) and T is pinned over the list only: one histogram of d = key - g in bins 2^kCandShift
+// wide (the candidates share their leading key bits, so digits of the key itself would pile them
+// into a handful of bins) names the bin that holds T, and the few keys of that bin are ranked
+// directly (each wave by itself, one key per lane).  The full path runs instead if fewer than k
+// keys reach g or a wave's part of the list overflows; the three plain levels run over the list
+// if T's bin holds more than 64 keys or T lies too far above g for the bins.  The result is the
+// same every way.  When every key equal to T belongs to the set (nearly always: T is alone) the
+// bitmap pass puts them into the set directly and the diff skips its tie phase.
 //
 // Dynamic LDS (s_dyn): three bitmaps of bm_words words, then list_cap (key, index) entries of 8 bytes (the diff's
 // staging lists take that room over once T is known).
 template <int VPT, int NT>
 __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSrc& src, int p, u32* s_dyn) {
   constexpr int NV = VPT;
-  __shared__ u32 s_hist[kHistCopies * kHistPitch];
+  __shared__ __align__(16) u32 s_hist[kHistCopies * kHistPitch];
   __shared__ int s_wave[64];
   __shared__ int s_res[3];
   __shared__ u32 s_small[64];
@@ -1208,6 +1239,7 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
   u32* s_old = s_dyn + 2 * bm_words;
   u64* l_ent = reinterpret_cast<u64*>(s_dyn + 3 * bm_words);  // bm_words is even: 8-byte aligned
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool reused = A.reuse_flags[p] != 0;
   const v4u* kp4 = reinterpret_cast<const v4u*>(A.keys + (size_t)p * A.n_pad);
   const int n = (int)A.N;
   const int nvec = (n + 3) >> 2;  // n_pad is a multiple of 8192, so whole vectors can be read
@@ -1223,7 +1255,17 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
     const int v = tid + i * NT;
     kreg[i] = v < nvec ? kp4[v] : v4u{0, 0, 0, 0};
   }
-  for (int i = tid; i < bm_words; i += NT) s_old[i] = 0;
+  // requested now, used by the diff at the end
+  const bool was_valid = A.valid[p] != 0;
+  int pre_tok[4];
+  diff_slot_tokens<NT>(A.slot_idx + (size_t)p * k_max, k, pre_tok);
+  // The gate's verdict is looked at only now, with the key loads already on their way: a pair that missed does
+  // not wait for the flag and then again for its keys (a pair that reused drops the loads it never needed).
+  if (reused) {
+    report_cached_set(A.set_sorted, A.topk_idx, A.hit_mask, p, k, k_max);
+    return;
+  }
+  lds_zero<NT>(s_dyn, 3 * bm_words);  // the three bitmaps are adjacent
 
   int need = k, above;
   u32 prefix = 0;
@@ -1236,7 +1278,8 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
   bool all_ties = false;  // uniform: every key equal to the k-th key belongs to the set and is already in s_new
   u32 bound = 0;
   if (A.r_sample > 0) {
-    for (int i = tid; i < 4096; i += NT) s_hist[i] = 0;
+    // the sample's 4096 bins, and behind them the kCandBins bins of the candidates' first level
+    lds_zero<NT>(s_hist, 4096 + kCandBins);
     if (tid < 2) s_flag[tid] = 0;
     __syncthreads();
 #pragma unroll
@@ -1246,15 +1289,14 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
     }
     __syncthreads();
     bound = (u32)find_bin<NT, 1>(s_hist, 4096, A.r_sample, &above, s_wave, s_res) << 20;
-    // cleared for the candidates' first level (the barrier after the compaction publishes it)
-    for (int i = tid; i < kCandBins; i += NT) s_hist[i] = 0;
   }
   if (bound != 0u) {
     // Candidates (key >= bound) into the list as (key, index) entries.  The order of the list is irrelevant
     // (histograms and bitmaps do not depend on it): every wave appends to its own part of the list, each key slot
     // by ballot rank, and is the only reader of that part afterwards, so no count has to be exchanged first.  The
     // last entry of a part only catches what does not fit; a wave that gets that far calls the guided path off.
-    const int part = A.list_cap / NW;
+    constexpr int kMine = 8;  // a lane's share of its wave's entries
+    const int part = min(A.list_cap / NW, 64 * kMine);
     u64* my_ent = l_ent + wave * part;
     int n_mine = 0;  // wave-uniform
 #pragma unroll
@@ -1275,25 +1317,39 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
       n_mine = 0;
       if (lane == 0) s_flag[0] = 1;
     }
-    for (int i = tid; i < 2 * bm_words; i += NT) s_new[i] = 0;  // s_new and s_eq are adjacent
-    __syncthreads();
+    // From here on a lane keeps its share of the wave's entries (lane, lane + 64, ...) in registers.
+    u32 ekey[kMine];
+    int eidx[kMine];
+#pragma unroll
+    for (int i = 0; i < kMine; ++i) {
+      u64 ent = 0ull;  // key 0: below every bound
+      if (i * 64 < n_mine)  // wave-uniform: the rounds past the wave's count cost a scalar branch
+        if (i * 64 + lane < n_mine) ent = my_ent[i * 64 + lane];
+      ekey[i] = (u32)(ent >> 32);
+      eidx[i] = (int)(u32)ent;
+    }
     // All candidates share the leading key bits, so the radix digit is taken from d = key - bound: d >> kCandShift
-    // in kCandBins bins (the last bin also takes everything further up).
-    for (int e = lane; e < n_mine; e += 64)
-      atomicAdd(&s_hist[min(((u32)(my_ent[e] >> 32) - bound) >> kCandShift, (u32)kCandBins - 1u)], 1u);
+    // in kCandBins bins (the last bin also takes everything further up).  A wave counts its own entries: no
+    // barrier since the compaction.
+    u32* const hist1 = s_hist + 4096;
+#pragma unroll
+    for (int i = 0; i < kMine; ++i)
+      if (i * 64 < n_mine)
+        if (ekey[i] != 0u) atomicAdd(&hist1[min((ekey[i] - bound) >> kCandShift, (u32)kCandBins - 1u)], 1u);
     __syncthreads();
     int in_bin;
-    const int b1 = find_bin<NT, 1>(s_hist, kCandBins, k, &above, s_wave, s_res, nullptr, &in_bin);
+    const int b1 = find_bin<NT, 1>(hist1, kCandBins, k, &above, s_wave, s_res, nullptr, &in_bin);
     // b1 >= 0: at least k candidates, which proves that the k-th key is among them
     guided = b1 >= 0 && s_flag[0] == 0;
     if (guided) {
       if (b1 != kCandBins - 1 && in_bin <= 64) {
         // The k-th key is one of the few keys of bin b1: they are gathered and every wave ranks them by itself.
         need -= above;
-        for (int e = lane; e < n_mine; e += 64) {
-          const u32 key = (u32)(my_ent[e] >> 32);
-          if (((key - bound) >> kCandShift) == (u32)b1) s_small[atomicAdd(&s_flag[1], 1)] = key;
-        }
+        const u32 lo = bound + ((u32)b1 << kCandShift);
+#pragma unroll
+        for (int i = 0; i < kMine; ++i)
+          if (i * 64 < n_mine)
+            if (ekey[i] - lo < (1u << kCandShift)) s_small[atomicAdd(&s_flag[1], 1)] = ekey[i];
         __syncthreads();
         const int n_small = __builtin_amdgcn_readfirstlane(in_bin);
         const u32 v = lane < n_small ? s_small[lane] : 0u;
@@ -1315,26 +1371,25 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
         for (int level = 0; level < 3; ++level) {
           for (int i = tid; i < kBins; i += NT) s_hist[i] = 0;
           __syncthreads();
-          for (int e = lane; e < n_mine; e += 64) {
-            const u32 key = (u32)(my_ent[e] >> 32);
-            if (level == 0 || (key >> level_shift(level)) == prefix)
-              atomicAdd(&s_hist[(key >> level_sub(level)) & level_mask(level)], 1u);
-          }
+#pragma unroll
+          for (int i = 0; i < kMine; ++i)
+            if (ekey[i] != 0u && (level == 0 || (ekey[i] >> level_shift(level)) == prefix))
+              atomicAdd(&s_hist[(ekey[i] >> level_sub(level)) & level_mask(level)], 1u);
           __syncthreads();
           const u32 bsel = (u32)find_bin<NT, 1>(s_hist, level == 2 ? 1024 : kBins, need, &above, s_wave, s_res);
           need -= above;
           prefix = level == 0 ? bsel : (prefix << (level == 1 ? 11 : 10)) | bsel;
         }
       }
-      const u32 T = prefix;
-      for (int e = lane; e < n_mine; e += 64) {
-        const u64 ent = my_ent[e];
-        const u32 key = (u32)(ent >> 32);
-        const int idx = (int)(u32)ent;
-        if (key > T || (all_ties && key == T))
-          atomicOr(&s_new[idx >> 5], 1u << (idx & 31));
-        else if (key == T)
-          atomicOr(&s_eq[idx >> 5], 1u << (idx & 31));
+      const u32 T = prefix;  // >= bound > 0: the empty entries (key 0) fall through
+#pragma unroll
+      for (int i = 0; i < kMine; ++i) {
+        if (i * 64 < n_mine) {
+          if (ekey[i] > T || (all_ties && ekey[i] == T))
+            atomicOr(&s_new[eidx[i] >> 5], 1u << (eidx[i] & 31));
+          else if (ekey[i] == T)
+            atomicOr(&s_eq[eidx[i] >> 5], 1u << (eidx[i] & 31));
+        }
       }
     }
   }
@@ -1385,7 +1440,7 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
   // 65536 keys = 2048 bitmap words.  The candidate list is dead by now: its room stages the diff's lists if
   // they fit.
 #define QSAC_DIFF_ARGS                                                                                              \
-  s_new, s_eq, s_old, A.valid[p] != 0, need, words, k, A.slot_idx + (size_t)p * k_max,                              \
+  s_new, s_eq, s_old, was_valid, need, words, k, A.slot_idx + (size_t)p * k_max,                                    \
       A.set_sorted + (size_t)p * k_max, A.topk_idx + (size_t)p * k, A.hit_mask + (size_t)p * k,                      \
       A.miss_slot + (size_t)p * k_max, A.miss_tok + (size_t)p * k_max, A.fetch_tok + (size_t)p * k_max,              \
       A.miss_count + p, A.valid + p, A.stats, src.slot[p % A.Hkv] >= 0, src.host_row_bytes, s_wave
@@ -1396,22 +1451,17 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
     st.mt = room + k;
     st.tk = room + 2 * k;
     st.hm = reinterpret_cast<uint8_t*>(room + 3 * k);
-    diff_phases<NT, 2048 / NT, true>(QSAC_DIFF_ARGS, st, all_ties);
+    diff_phases<NT, 2048 / NT, true>(QSAC_DIFF_ARGS, st, all_ties, pre_tok);
   } else {
-    diff_phases<NT, 2048 / NT, false>(QSAC_DIFF_ARGS, DiffStage(), all_ties);
+    diff_phases<NT, 2048 / NT, false>(QSAC_DIFF_ARGS, DiffStage(), all_ties, pre_tok);
   }
 #undef QSAC_DIFF_ARGS
 }
 
 template <int VPT, int NT>
 __global__ __launch_bounds__(NT) void qsac_select_small_kernel(SelArgs A, FillSrc src) {
-  extern __shared__ u32 s_dyn[];
-  const int p = blockIdx.x;
-  if (A.reuse_flags[p]) {
-    report_cached_set(A.set_sorted, A.topk_idx, A.hit_mask, p, A.k, A.k_max);
-    return;
-  }
-  select_small_body<VPT, NT>(A, src, p, s_dyn);
+  extern __shared__ __align__(16) u32 s_dyn[];
+  select_small_body<VPT, NT>(A, src, blockIdx.x, s_dyn);
 }
 
 // ---------------------------------------------------------------- fill
