@@ -250,11 +250,11 @@ def test_ties_on_the_long_context_path(H):
     sess.close()
 
 
-def exact_tie_case(H, flags):
+def exact_tie_case(H, flags, N=5000, k=257):
     """K entries in {-1, 0, 1} and queries with a few small-integer entries: every score is a small
     integer, exact in fp32 and fp64 alike, with hundreds of exact ties across the k-th score - the
     index sets must match exactly under the lowest-index tie-break."""
-    B, Hq, Hkv, N, k = 1, 4, 2, 5000, 257
+    B, Hq, Hkv = 1, 4, 2
     rng = np.random.default_rng(99)
     K = torch.from_numpy(rng.integers(-1, 2, (B, Hkv, N, 128)).astype(np.float32)).to(torch.bfloat16)
     V = torch.from_numpy(rng.standard_normal((B, Hkv, N, 128)).astype(np.float32)).to(torch.bfloat16)
@@ -271,12 +271,23 @@ def exact_tie_case(H, flags):
             kth = r.kth_score[p]
             assert (r.scores[p] == kth).sum() > 20          # the k-th score really is tied
     assert par.n_band == 0
+    st = sess.stats()
     sess.close()
+    return st
 
 
 @pytest.mark.parametrize("flags", [0, Q.QSAC_FLAG_SCORE_VALU])
 def test_exact_ties_take_the_lowest_index(H, flags):
     exact_tie_case(H, flags)
+
+
+def test_exact_ties_inside_the_candidate_list(H):
+    """The same integer scores at a size where the one-workgroup select works on its candidate list: the bin
+    of the k-th key holds hundreds of equal keys (more than one wave can rank directly), of which only the first
+    few by index belong to the set."""
+    st = exact_tie_case(H, 0, N=20000, k=1000)
+    print("guided selects", st["guided_selects"], "of", st["miss_heads"], flush=True)
+    assert st["guided_selects"] > 0
 
 
 def test_all_keys_equal_selects_the_first_k(H):
@@ -358,6 +369,47 @@ def test_guided_select(H, N, k, k_max):
     """The one-workgroup select takes its top-k from the keys above a sampled bound when it can, and from all
     keys when it cannot (k = N, k too large for the candidate list): sets, masks and slots against the oracle."""
     par = run_chain(H, B=3, Hq=8, Hkv=2, N=N, k=k, k_max=k_max, dtype="bf16", steps=12, seed=77, side_stream=False)
+
+
+def outstanding_rows_case(H, N, k, special, scale):
+    """Keys at `special` score `scale` times what the others do (all along one direction d, queries along d)."""
+    B, Hq, Hkv = 1, 4, 1
+    g = torch.Generator().manual_seed(21)
+    K = torch.randn((B, Hkv, N, 128), generator=g)
+    d = torch.randn(128, generator=g)
+    d = d / d.norm()
+    K[0, 0, special] = scale * d + 0.05 * torch.randn((len(special), 128), generator=g)
+    K = K.to(torch.bfloat16)
+    V = torch.randn((B, Hkv, N, 128), generator=g).to(torch.bfloat16)
+    sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, N, k, "bf16", K=K, V=V, side_stream=False)
+    par = H.Parity(sess, "bf16", Kb, Ksb, Vsb)
+    rng = np.random.default_rng(22)
+    for t in range(4):
+        q = np.tile(d.double().numpy(), (B, Hq, 1)) + 0.05 * rng.standard_normal((B, Hq, 128))
+        par.step(q, 2.0, k, label=f"outstanding rows step {t}")
+    st = sess.stats()
+    sess.close()
+    return st
+
+
+def test_guided_select_with_the_kth_key_far_above_the_bound(H):
+    """1500 keys score a hundred times what the rest do, none of them where the select samples, and k = 512:
+    the sampled bound lies among the ordinary keys, the k-th key octaves above it, beyond what the candidates'
+    histogram resolves, so the radix levels over the candidate list decide."""
+    N, k = 32768, 512
+    unsampled = np.setdiff1d(np.arange(N), 4 * np.arange(N // 4))
+    special = np.random.default_rng(5).choice(unsampled, 1500, replace=False)
+    st = outstanding_rows_case(H, N, k, special, 100.0)
+    assert st["miss_heads"] == 4 and st["guided_selects"] == 4
+
+
+def test_guided_select_when_one_wave_holds_too_many_candidates(H):
+    """768 outstanding keys in the three 256-token stripes that one wave of the select reads (tokens 0..255 of
+    every 4096): that wave's part of the candidate list overflows and the full radix path takes over."""
+    N, k = 32768, 2048
+    special = np.concatenate([np.arange(4096 * j, 4096 * j + 256) for j in range(3)])
+    st = outstanding_rows_case(H, N, k, special, 40.0)
+    assert st["miss_heads"] == 4 and st["guided_selects"] == 0
 
 
 def test_calibration_kernels_run(H):
