@@ -1282,9 +1282,18 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
     lds_zero<NT>(s_hist, 4096 + kCandBins);
     if (tid < 2) s_flag[tid] = 0;
     __syncthreads();
+    constexpr int S = 4096 / NT;  // sample keys per thread, spread over its vectors
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const u32 key = NV >= 4 ? kreg[j * (NV / 4)].x : ((j & 1) ? kreg[(j >> 1) % NV].z : kreg[(j >> 1) % NV].x);
+    for (int j = 0; j < S; ++j) {
+      u32 key;
+      if (NV >= S) {
+        key = kreg[j * (NV / S)].x;
+      } else {
+        constexpr int per = S / (NV < S ? NV : S);  // 2 or 4 sample keys per vector
+        const v4u& q = kreg[(j / per) % NV];
+        const int c = (j % per) * (4 / per);
+        key = c == 0 ? q.x : c == 1 ? q.y : c == 2 ? q.z : q.w;
+      }
       atomicAdd(&s_hist[key >> 20], 1u);
     }
     __syncthreads();
@@ -1295,7 +1304,7 @@ __device__ __forceinline__ void select_small_body(const SelArgs& A, const FillSr
     // (histograms and bitmaps do not depend on it): every wave appends to its own part of the list, each key slot
     // by ballot rank, and is the only reader of that part afterwards, so no count has to be exchanged first.  The
     // last entry of a part only catches what does not fit; a wave that gets that far calls the guided path off.
-    constexpr int kMine = 8;  // a lane's share of its wave's entries
+    constexpr int kMine = kSelectListCap / NT;  // a lane's share of its wave's entries
     const int part = min(A.list_cap / NW, 64 * kMine);
     u64* my_ent = l_ent + wave * part;
     int n_mine = 0;  // wave-uniform
