@@ -98,7 +98,9 @@ void make_layout(const qsac_config* c, qsac_ws_layout* L) {
   L->set_sorted = take(P * c->k_max * 4);
   L->keys = take(P * n_pad * 4);
   L->hist = take(P * 3 * kBins * 4);
-  L->bm_new = take(P * words * 4);
+  // (the mid-N select keeps the pairs' candidate lists where the grid-wide path has its first bitmap)
+  const bool mid_n = (size_t)c->n_ctx > (size_t)kSmallMaxN && (size_t)c->n_ctx <= (size_t)kStreamMaxN;
+  L->bm_new = take(mid_n ? std::max(P * words * 4, P * (size_t)kStreamListCap * 8) : P * words * 4);
   L->bm_eq = take(P * words * 4);
   L->bm_old = take(P * words * 4);
   L->miss_count = take(P * 4);
@@ -293,6 +295,7 @@ int clear_state(qsac_ctx* c) {
   qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.valid), (size_t)c->P);
   qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.stats), (size_t)16);
   qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.miss_count), (size_t)c->P);
+  qsac_zero_kernel<<<1, 256, 0, c->s_main>>>(reinterpret_cast<u32*>(ws + c->L.sel_r), (size_t)c->P * kSelStride);
   HIP_TRY(hipGetLastError());
   c->k_bound = 0;
   c->steps = 0;
@@ -323,6 +326,8 @@ int raise_lds_limits() {
                        (const void*)qsac_select_small_kernel<8, 1024>, (const void*)qsac_select_small_kernel<16, 1024>,
                        (const void*)qsac_diff_list_kernel};
   for (const void* fn : fns) HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_max));
+  HIP_TRY(hipFuncSetAttribute((const void*)qsac_select_stream_kernel<1024>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)(((size_t)(kStreamMaxN / 32) * 3 + 2 * (size_t)kSelectListCap) * sizeof(u32))));
   return QSAC_OK;
 }
 
@@ -701,8 +706,8 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
   }
   // 3. select the k best, diff against the cache slots
   mark(2);
-  if (c->small) {
-    // key vectors per thread that keep the pair's keys in registers
+  if (N <= kStreamMaxN) {
+    // one workgroup per pair: the keys in its registers (vpt key vectors per thread), or streamed
     const int64_t nvec = (N + 3) / 4;
     const int vpt = nvec <= 2 * kDiffThreads ? 2 : nvec <= 4 * kDiffThreads ? 4 : nvec <= 8 * kDiffThreads ? 8 : 16;
     SelArgs S;
@@ -725,8 +730,14 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
     S.k_max = k_max;
     S.bm_words = (int)((N + 63) / 64 * 2);
     S.list_cap = kSelectListCap;
-    S.r_sample = select_sample_rank(k, vpt);
+    S.r_sample = c->small ? select_sample_rank(k, vpt) : 0;
     const size_t lds_sel = ((size_t)S.bm_words * 3 + 2 * (size_t)kSelectListCap) * sizeof(u32);
+    if (!c->small) {
+      // the first bitmap region of the grid-wide path (unused here, sized for this) holds the pairs' lists
+      const dim3 grid((unsigned)((N + 4 * kStreamChunkVec * 1024 - 1) / (4 * kStreamChunkVec * 1024)), (unsigned)P);
+      qsac_select_stream_kernel<1024><<<grid, 1024, lds_sel, sm>>>(S, hist, reinterpret_cast<u64*>(bm_new),
+                                                                  kStreamListCap, sel_r, src);
+    } else
     switch (vpt) {
       case 2: qsac_select_small_kernel<2, 1024><<<P, 1024, lds_sel, sm>>>(S, src); break;
       case 4: qsac_select_small_kernel<4, 1024><<<P, 1024, lds_sel, sm>>>(S, src); break;

@@ -1473,6 +1473,331 @@ __global__ __launch_bounds__(NT) void qsac_select_small_kernel(SelArgs A, FillSr
   select_small_body<VPT, NT>(A, src, blockIdx.x, s_dyn);
 }
 
+// Mid-N path (kSmallMaxN < N <= kStreamMaxN): the keys of a pair no longer fit one workgroup's registers, but its
+// bitmaps still fit one workgroup's LDS.  The scoring kernel has left the exact level-0 histogram (top 11 key
+// bits); its bin b0 of the k-th key T splits the keys into "above b0" (in the set for sure), "below" (out) and the
+// bin's own keys, the only undecided ones.
+//
+// Grid (chunks of 4 * kStreamChunkVec * NT keys, pairs), NT threads.  Every workgroup of a pair derives b0 (same histogram, same
+// answer) and appends its chunk's keys at or above the bin to the pair's list in the workspace (`glist`: a wave
+// reserves room with one atomic add and fills it by ballot rank; the list's length is known beforehand from the
+// histogram).  The workgroup that finishes last (a counter per pair; entries and counter are device-scope atomics) goes on
+// alone: entries above the bin go straight into the "selected" bitmap in LDS, T is pinned over the rest by one
+// histogram of the bits below the bin's and a direct rank among the few keys of T's fine bin (or one more level
+// if they are many), then bitmaps and the diff, as in the small-N path.  Nobody waits for anybody: the other
+// workgroups are gone by then.
+//
+// If the histogram says the list would not hold the keys at or above the bin (heavy ties), workgroup 0 of the pair
+// does the job alone, streaming the pair's keys (they were just written and sit in the L2) as often as it takes:
+// a histogram pass descends one radix level (11, then 10 bits), and as soon as the bin of T holds few enough keys
+// they are compacted into an LDS list (each wave its own part, as in the small-N path) and treated as above; after
+// the last level T is known exactly and one more pass turns "key > T" and "key == T" into the bitmaps.
+// Same result as the grid-wide kernels, which keep the contexts above kStreamMaxN.
+//
+// sync: kSelStride ints per pair, [0] list entries reserved, [1] workgroups done; zero between launches (the last
+// workgroup leaves them so).  Dynamic LDS (s_dyn): three bitmaps of bm_words words, then list_cap entries of 8 bytes.
+constexpr int kStreamMaxN = 131072;   // three bitmaps of N bits, the list and the histogram share the LDS
+constexpr int kStreamLimit = 4096;    // undecided keys the compaction into LDS is tried with (half the list)
+constexpr int kStreamChunkVec = 8;    // key vectors per thread of a workgroup's chunk (32768 keys with 1024 threads)
+constexpr int kStreamListCap = 16384; // entries of a pair's list in the workspace (the last workgroup holds them in registers)
+
+template <int NT>
+__global__ __launch_bounds__(NT) void qsac_select_stream_kernel(SelArgs A, const u32* __restrict__ hist,
+                                                                u64* __restrict__ glist, int gcap,
+                                                                int* __restrict__ sync, FillSrc src) {
+  extern __shared__ __align__(16) u32 s_dyn[];
+  __shared__ __align__(16) u32 s_hist[kCandBins];
+  __shared__ int s_wave[64];
+  __shared__ int s_res[3];
+  __shared__ u32 s_small[64];
+  __shared__ int s_flag[3];  // [0] a wave ran out of list room, [1] keys gathered in s_small, [2] arrival ticket
+  constexpr int NW = NT / 64;
+  constexpr int kMine = kStreamListCap / NT;  // entries a thread keeps in registers
+  constexpr int kBatch = 8;                   // key vectors a thread has in flight when streaming
+  const int p = blockIdx.y, chunk = blockIdx.x, n_chunks = gridDim.x;
+  const int bm_words = A.bm_words, k = A.k, k_max = A.k_max;
+  if (A.reuse_flags[p]) {
+    if (chunk == 0) report_cached_set(A.set_sorted, A.topk_idx, A.hit_mask, p, k, k_max);
+    return;
+  }
+  u32* s_new = s_dyn;
+  u32* s_eq = s_dyn + bm_words;
+  u32* s_old = s_dyn + 2 * bm_words;
+  u64* l_ent = reinterpret_cast<u64*>(s_dyn + 3 * bm_words);  // bm_words is even: 8-byte aligned
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const v4u* kp4 = reinterpret_cast<const v4u*>(A.keys + (size_t)p * A.n_pad);
+  const int n = (int)A.N;
+  const int nvec = (n + 3) >> 2;  // keys past N inside the last vector are 0: below every bin that matters
+  const int words = (n + 31) >> 5;
+
+  // this workgroup's chunk of the keys, requested before the histogram is looked at (a workgroup that turns out
+  // to have nothing to do drops them)
+  v4u q[kStreamChunkVec];
+#pragma unroll
+  for (int u = 0; u < kStreamChunkVec; ++u) {
+    const int v = (chunk * kStreamChunkVec + u) * NT + tid;
+    q[u] = v < nvec ? kp4[v] : v4u{0, 0, 0, 0};
+  }
+  // level 0 comes from the scoring kernel: bits 31..21
+  int need = k, above = 0, in_bin = 0;
+  u32 prefix = (u32)find_bin<NT, 1>(hist + (size_t)p * 3 * kBins, kBins, need, &above, s_wave, s_res, nullptr, &in_bin);
+  need -= above;
+  int shift = 21;  // key >> shift == prefix names the bin of T; 0 once T is known exactly
+  const int n_list = above + in_bin;  // keys at or above the bin
+  const bool shared = n_list <= min(gcap, kStreamListCap);
+
+  u32 ekey[kMine];  // the entries this thread works on (key 0: none)
+  int eidx[kMine];
+  int my_rounds = 0;  // rounds of ekey / eidx that may hold entries (wave-uniform)
+  bool have_list = false;
+  bool was_valid = false;
+  int pre_tok[4] = {0, 0, 0, 0};
+
+  if (shared) {
+    u64* gl = glist + (size_t)p * gcap;
+    int* sy = sync + (size_t)p * kSelStride;
+    int cnt = 0;
+#pragma unroll
+    for (int u = 0; u < kStreamChunkVec; ++u)
+      cnt += __popcll(__ballot((q[u].x >> 21) >= prefix)) + __popcll(__ballot((q[u].y >> 21) >= prefix)) +
+             __popcll(__ballot((q[u].z >> 21) >= prefix)) + __popcll(__ballot((q[u].w >> 21) >= prefix));
+    int at = 0;
+    if (cnt > 0) {  // wave-uniform
+      if (lane == 0) at = __hip_atomic_fetch_add(&sy[0], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      at = __builtin_amdgcn_readfirstlane(at);
+#pragma unroll
+      for (int u = 0; u < kStreamChunkVec; ++u) {
+        const int v = (chunk * kStreamChunkVec + u) * NT + tid;
+        const u32 ks[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool c = (ks[j] >> 21) >= prefix;
+          const u64 m = __ballot(c);
+          if (c) {
+            const int pos = (int)__builtin_amdgcn_mbcnt_hi((u32)(m >> 32), __builtin_amdgcn_mbcnt_lo((u32)m, (u32)at));
+            if (pos < gcap)  // (the histogram promises that it fits)
+              __hip_atomic_store(&gl[pos], ((u64)ks[j] << 32) | (u32)(4 * v + j), __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
+          }
+          at += __popcll(m);
+        }
+      }
+    }
+    // The entries travel as device-scope atomic stores and loads (they pass the L2 of the XCD they were written
+    // on), and every store of this workgroup has been acknowledged before it counts itself done: no fence, which
+    // here would write back and invalidate a whole L2 under the feet of the workgroups still reading keys.  The
+    // last workgroup to arrive goes on.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (tid == 0) s_flag[2] = __hip_atomic_fetch_add(&sy[1], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_flag[2] != n_chunks - 1) return;
+    if (tid == 0) {
+      sy[0] = 0;
+      sy[1] = 0;
+    }
+    was_valid = A.valid[p] != 0;
+    diff_slot_tokens<NT>(A.slot_idx + (size_t)p * k_max, k, pre_tok);
+    lds_zero<NT>(s_dyn, 3 * bm_words);
+    if (tid < 2) s_flag[tid] = 0;
+    my_rounds = (n_list + NT - 1) / NT;
+#pragma unroll
+    for (int i = 0; i < kMine; ++i) {
+      u64 ent = 0ull;
+      if (i < my_rounds)
+        if (i * NT + tid < n_list) ent = __hip_atomic_load(&gl[i * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ekey[i] = (u32)(ent >> 32);
+      eidx[i] = (int)(u32)ent;
+    }
+    __syncthreads();
+    // entries above the bin are in the set for sure
+#pragma unroll
+    for (int i = 0; i < kMine; ++i)
+      if (i < my_rounds)
+        if ((ekey[i] >> 21) > prefix) {
+          atomicOr(&s_new[eidx[i] >> 5], 1u << (eidx[i] & 31));
+          ekey[i] = 0u;
+        }
+    have_list = true;
+  } else {
+    if (chunk != 0) return;
+    was_valid = A.valid[p] != 0;
+    diff_slot_tokens<NT>(A.slot_idx + (size_t)p * k_max, k, pre_tok);
+    lds_zero<NT>(s_dyn, 3 * bm_words);
+    // f(key, index) for every key of the pair, kBatch vector loads per thread in flight; uniform trip count, all
+    // lanes active in f (vectors past the end read as zeros)
+    auto stream = [&](auto&& f) {
+      for (int v0 = 0; v0 < nvec; v0 += kBatch * NT) {
+        v4u kq[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const int v = v0 + u * NT + tid;
+          kq[u] = v < nvec ? kp4[v] : v4u{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const int v = v0 + u * NT + tid;
+          f(kq[u].x, 4 * v);
+          f(kq[u].y, 4 * v + 1);
+          f(kq[u].z, 4 * v + 2);
+          f(kq[u].w, 4 * v + 3);
+        }
+      }
+    };
+    const int part = A.list_cap / NW;  // at most 64 * kMine
+    u64* my_ent = l_ent + wave * part;
+    int n_mine = 0;  // wave-uniform
+    for (;;) {
+      if (in_bin <= kStreamLimit && shift > 0) {
+        __syncthreads();
+        if (tid < 2) s_flag[tid] = 0;
+        __syncthreads();
+        n_mine = 0;
+        stream([&](u32 key, int idx) {
+          const u32 top = key >> shift;
+          if (top > prefix) atomicOr(&s_new[idx >> 5], 1u << (idx & 31));  // fewer than k keys in all
+          const bool c = top == prefix;
+          const u64 m = __ballot(c);
+          if (c) {
+            const int pos = (int)__builtin_amdgcn_mbcnt_hi((u32)(m >> 32), __builtin_amdgcn_mbcnt_lo((u32)m, (u32)n_mine));
+            my_ent[min(pos, part - 1)] = ((u64)key << 32) | (u32)idx;
+          }
+          n_mine += __popcll(m);
+        });
+        if (n_mine > part - 1 && lane == 0) s_flag[0] = 1;
+        __syncthreads();
+        if (s_flag[0] == 0) {
+          have_list = true;
+          break;
+        }
+      }
+      if (shift == 0) break;
+      // one radix level down: bits 20..10, then bits 9..0
+      const int sub = shift == 21 ? 10 : 0;
+      const int nb = shift == 21 ? kBins : 1024;
+      __syncthreads();
+      lds_zero<NT>(s_hist, nb);
+      __syncthreads();
+      stream([&](u32 key, int) {
+        if ((key >> shift) == prefix) atomicAdd(&s_hist[(key >> sub) & (u32)(nb - 1)], 1u);
+      });
+      __syncthreads();
+      const u32 b = (u32)find_bin<NT, 1>(s_hist, nb, need, &above, s_wave, s_res, nullptr, &in_bin);
+      need -= above;
+      prefix = (prefix << (shift - sub)) | b;
+      shift = sub;
+    }
+    if (have_list) {
+      my_rounds = (n_mine + 63) >> 6;
+#pragma unroll
+      for (int i = 0; i < kMine; ++i) {
+        u64 ent = 0ull;
+        if (i < my_rounds)
+          if (i * 64 + lane < n_mine) ent = my_ent[i * 64 + lane];
+        ekey[i] = (u32)(ent >> 32);
+        eidx[i] = (int)(u32)ent;
+      }
+    } else {
+      // T = prefix is known exactly; `need` of the keys equal to it belong to the set
+      const u32 T = prefix;
+      stream([&](u32 key, int idx) {
+        if (key > T)
+          atomicOr(&s_new[idx >> 5], 1u << (idx & 31));
+        else if (key == T)
+          atomicOr(&s_eq[idx >> 5], 1u << (idx & 31));
+      });
+    }
+  }
+
+  bool all_ties = false;  // uniform: every key equal to T belongs to the set and is already in s_new
+  if (have_list) {
+    // The entries share the bits above `shift`; T is pinned by the bits below.  First the top 12 of them (all of
+    // them if there are no more) in kCandBins bins.
+    const u32 lo = prefix << shift;
+    const int cshift = shift > 12 ? shift - 12 : 0;
+    __syncthreads();
+    lds_zero<NT>(s_hist, kCandBins);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kMine; ++i)
+      if (i < my_rounds)
+        if (ekey[i] != 0u) atomicAdd(&s_hist[(ekey[i] - lo) >> cshift], 1u);
+    __syncthreads();
+    const u32 b1 = (u32)find_bin<NT, 1>(s_hist, kCandBins, need, &above, s_wave, s_res, nullptr, &in_bin);
+    need -= above;
+    const u32 lo1 = lo + (b1 << cshift);  // T lies in [lo1, lo1 + 2^cshift)
+    if (cshift == 0) {
+      prefix = lo1;
+      all_ties = need == in_bin;
+    } else if (in_bin <= 64) {
+      // the few keys of that bin are gathered and every wave ranks them by itself
+#pragma unroll
+      for (int i = 0; i < kMine; ++i)
+        if (i < my_rounds)
+          if (ekey[i] - lo1 < (1u << cshift)) s_small[atomicAdd(&s_flag[1], 1)] = ekey[i];
+      __syncthreads();
+      const int n_small = __builtin_amdgcn_readfirstlane(in_bin);
+      const u32 v = lane < n_small ? s_small[lane] : 0u;
+      int gt = 0, eq = 0;  // keys of the bin above / equal to this lane's (itself included)
+      for (int j = 0; j < n_small; ++j) {
+        const u32 x = (u32)__builtin_amdgcn_readlane((int)v, j);
+        gt += (int)(x > v);
+        eq += (int)(x == v);
+      }
+      const u64 holds = __ballot(lane < n_small && gt < need && need <= gt + eq);
+      const int from = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)holds) - 1);
+      prefix = (u32)__builtin_amdgcn_readlane((int)v, from);
+      need -= __builtin_amdgcn_readlane(gt, from);
+      all_ties = need == __builtin_amdgcn_readlane(eq, from);
+    } else {
+      // one more level over the list: the cshift (at most 9) bits left, in 1024 bins
+      lds_zero<NT>(s_hist, 1024);
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < kMine; ++i)
+        if (i < my_rounds)
+          if (ekey[i] - lo1 < (1u << cshift)) atomicAdd(&s_hist[ekey[i] - lo1], 1u);
+      __syncthreads();
+      const u32 b2 = (u32)find_bin<NT, 1>(s_hist, 1024, need, &above, s_wave, s_res, nullptr, &in_bin);
+      need -= above;
+      prefix = lo1 + b2;
+      all_ties = need == in_bin;
+    }
+    const u32 T = prefix;  // > 0: the empty entries (key 0) fall through
+#pragma unroll
+    for (int i = 0; i < kMine; ++i) {
+      if (i < my_rounds) {
+        if (ekey[i] > T || (all_ties && ekey[i] == T))
+          atomicOr(&s_new[eidx[i] >> 5], 1u << (eidx[i] & 31));
+        else if (ekey[i] == T)
+          atomicOr(&s_eq[eidx[i] >> 5], 1u << (eidx[i] & 31));
+      }
+    }
+  }
+  if (tid == 0 && have_list) atomicAdd(&A.stats[6], 1ull);
+  __syncthreads();
+  // kStreamMaxN keys = 4096 bitmap words.  The candidate list is dead by now: its room stages the diff's lists if
+  // they fit.
+#define QSAC_DIFF_ARGS                                                                                              \
+  s_new, s_eq, s_old, was_valid, need, words, k, A.slot_idx + (size_t)p * k_max,                                    \
+      A.set_sorted + (size_t)p * k_max, A.topk_idx + (size_t)p * k, A.hit_mask + (size_t)p * k,                      \
+      A.miss_slot + (size_t)p * k_max, A.miss_tok + (size_t)p * k_max, A.fetch_tok + (size_t)p * k_max,              \
+      A.miss_count + p, A.valid + p, A.stats, src.slot[p % A.Hkv] >= 0, src.host_row_bytes, s_wave
+  if (3 * k + (k + 3) / 4 <= 2 * A.list_cap) {
+    int* const room = reinterpret_cast<int*>(l_ent);
+    DiffStage st;
+    st.ms = room;
+    st.mt = room + k;
+    st.tk = room + 2 * k;
+    st.hm = reinterpret_cast<uint8_t*>(room + 3 * k);
+    diff_phases<NT, kStreamMaxN / 32 / NT, true>(QSAC_DIFF_ARGS, st, all_ties, pre_tok);
+  } else {
+    diff_phases<NT, kStreamMaxN / 32 / NT, false>(QSAC_DIFF_ARGS, DiffStage(), all_ties, pre_tok);
+  }
+#undef QSAC_DIFF_ARGS
+}
+
 // ---------------------------------------------------------------- fill
 
 // Copies the rows named by a pair's miss list into its slots.  A 16-lane group moves one
