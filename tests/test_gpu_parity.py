@@ -412,6 +412,39 @@ def test_guided_select_when_one_wave_holds_too_many_candidates(H):
     assert st["miss_heads"] == 4 and st["guided_selects"] == 0
 
 
+@pytest.mark.parametrize("N", [32768, 100000])
+def test_partial_ties_among_the_candidates(H, N):
+    """200 identical key rows score highest and k = 100: the k-th key's fine bin holds more equal keys than a wave
+    ranks directly, and only the first 100 of them by index belong to the set (one-workgroup select at 32768,
+    list-building select at 100000)."""
+    B, Hq, Hkv, k = 1, 4, 1, 100
+    g = torch.Generator().manual_seed(31)
+    K = torch.randn((B, Hkv, N, 128), generator=g)
+    row = 3.0 * torch.randn(128, generator=g)
+    twins = np.sort(np.random.default_rng(32).choice(N, 200, replace=False))
+    K[0, 0, twins] = row
+    K = K.to(torch.bfloat16)
+    V = torch.randn((B, Hkv, N, 128), generator=g).to(torch.bfloat16)
+    sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, N, k, "bf16", K=K, V=V, side_stream=False)
+    par = H.Parity(sess, "bf16", Kb, Ksb, Vsb)
+    rng = np.random.default_rng(33)
+    base = K[0, 0, twins[0]].double().numpy()
+    for t in range(3):
+        q = np.tile(base / np.linalg.norm(base), (B, Hq, 1)) + 0.01 * rng.standard_normal((B, Hq, 128))
+        r = par.step(q, 2.0, k, label=f"partial ties N={N} step {t}")
+        assert (r.scores[0] == r.kth_score[0]).sum() == 200
+        assert sess.topk_idx.cpu().numpy().reshape(-1).tolist() == twins[:k].tolist()
+    assert par.n_band == 0 and sess.stats()["guided_selects"] == 3
+    sess.close()
+
+
+@pytest.mark.parametrize("N,k", [(100000, 20000), (131072, 40000), (70000, 9000)])
+def test_list_building_select_with_large_k(H, N, k):
+    """More keys at or above the k-th key's level-0 bin than the pairs' lists hold: one workgroup streams the
+    keys, descends a radix level and compacts what is left into LDS (or, at 9000, stays with the list)."""
+    run_chain(H, B=1, Hq=4, Hkv=1, N=N, k=k, k_max=k, dtype="bf16", steps=3, tau=2.0, expect_both=False, seed=41)
+
+
 def test_calibration_kernels_run(H):
     """The two measurement aids: the copy moves the bytes, the read-only kernel leaves its sink alone."""
     src = torch.arange(1 << 18, dtype=torch.int32, device="cuda:0")
