@@ -78,7 +78,7 @@ int select_sample_rank(int k, int vpt) {
   const int r = (int)std::ceil(x * x);
   const double upper = (double)vpt * (r + 6.0 * std::sqrt((double)r));
   // the bound is the lower edge of a histogram bin, which adds up to a bin's worth of keys: leave half the list
-  if (r > 2048 || upper > 0.5 * kSelectListCap) return 0;
+  if (r > 2048 || upper > 0.6 * kSelectListCap) return 0;
   return r;
 }
 
