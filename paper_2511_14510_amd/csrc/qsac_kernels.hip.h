@@ -607,6 +607,12 @@ __global__ __launch_bounds__(256) void qsac_refine_kernel(const uint8_t* __restr
   __shared__ int s_res[2];
   u32* hp = hist + (size_t)p * 3 * kBins;
   int* sp = sel + (size_t)p * kSelStride;
+  // this workgroup's keys are requested first, so that they travel while the bin of the level above is found
+  const int64_t base = (int64_t)blockIdx.x * kSelChunk;
+  const v4u* kp = reinterpret_cast<const v4u*>(keys + (size_t)p * n_pad + base);
+  v4u kreg[kSelChunk / 4 / 256];
+#pragma unroll
+  for (int i = 0; i < kSelChunk / 4 / 256; ++i) kreg[i] = kp[i * 256 + threadIdx.x];
   for (int i = threadIdx.x; i < kBins; i += 256) s_hist[i] = 0;
   int above;
   int need = k;
@@ -633,12 +639,10 @@ __global__ __launch_bounds__(256) void qsac_refine_kernel(const uint8_t* __restr
   }
   const u32 mask = (LEVEL == 1) ? 0x7ffu : 0x3ffu;
   const int sub = (LEVEL == 1) ? 10 : 0;
-  const int64_t base = (int64_t)blockIdx.x * kSelChunk;
-  const v4u* kp = reinterpret_cast<const v4u*>(keys + (size_t)p * n_pad + base);
 #pragma unroll
   for (int i = 0; i < kSelChunk / 4 / 256; ++i) {
     const int v = i * 256 + threadIdx.x;
-    v4u kk = kp[v];
+    const v4u kk = kreg[i];
     const int64_t n = base + (int64_t)v * 4;
     if (n + 0 < N && (kk.x >> shift) == prefix) atomicAdd(&s_hist[(kk.x >> sub) & mask], 1u);
     if (n + 1 < N && (kk.y >> shift) == prefix) atomicAdd(&s_hist[(kk.y >> sub) & mask], 1u);
@@ -670,6 +674,12 @@ __global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restric
   if (threadIdx.x < 2) s_cnt[threadIdx.x] = 0;  // find_bin's barriers come before its use
   const u32* hp = hist + (size_t)p * 3 * kBins;
   int* sp = sel + (size_t)p * kSelStride;
+  // this workgroup's keys are requested first, so that they travel while T is put together
+  const int64_t base = (int64_t)blockIdx.x * kSelChunk;
+  const u32* kp = keys + (size_t)p * n_pad;
+  u32 kreg[kSelChunk / 256];
+#pragma unroll
+  for (int i = 0; i < kSelChunk / 256; ++i) kreg[i] = kp[base + (int64_t)i * 256 + threadIdx.x];
   const u32 b0 = (u32)sp[1], b1 = (u32)sp[3];
   int above, need = sp[4];
   u32 b2 = (u32)find_bin<256>(hp + 2 * kBins, 1024, need, &above, s_wave, s_res);
@@ -678,17 +688,15 @@ __global__ __launch_bounds__(256) void qsac_mark_kernel(const uint8_t* __restric
   if (blockIdx.x == 0 && threadIdx.x == 0) sp[0] = need;
 
   const int lane = threadIdx.x & 63;
-  const int64_t base = (int64_t)blockIdx.x * kSelChunk;
-  const u32* kp = keys + (size_t)p * n_pad;
   u32* gt = bm_new + (size_t)p * words;
   u32* eq = bm_eq + (size_t)p * words;
   u32* old = bm_old + (size_t)p * words;
   const bool clear_old = chunk_cnt == nullptr;
   int cg = 0, ce = 0;  // lane 0: bits of this wave
-#pragma unroll 4
+#pragma unroll
   for (int i = 0; i < kSelChunk / 256; ++i) {
     const int64_t n = base + (int64_t)i * 256 + threadIdx.x;
-    const u32 key = kp[n];
+    const u32 key = kreg[i];
     const bool in = n < N;
     const u64 mg = __ballot(in && key > T);
     const u64 me = __ballot(in && key == T);
