@@ -85,8 +85,17 @@ enum {
                                 wait is bounded (qsac_config.push_wait_us): if the flag does not arrive in time the
                                 kernel records the fact and exits, the step's results are invalid, and the next call
                                 on the context returns QSAC_ETIMEOUT until qsac_reset                         */
-  QSAC_FLAG_PUSH_HOLD = 64   /* test aid for push mode: the transfer threads ignore every request, so every polling
+  QSAC_FLAG_PUSH_HOLD = 64,  /* test aid for push mode: the transfer threads ignore every request, so every polling
                                 kernel runs into its bound                                                  */
+  QSAC_FLAG_STAGGER = 128    /* staggered schedule (needs stream_side and batch >= 2; not with SERIAL, PROFILE,
+                                FILL_KERNEL or PUSH_FILL): after the gate, the batch runs in up to four slices
+                                that alternate between stream_main and stream_side, each starting when the one
+                                before it has finished scoring.  The slices are independent (Algorithm 1 is per
+                                head), so the results are those of the plain schedule up to the summation order of
+                                the attention splits; what changes is that a slice scores (HBM) while the slice
+                                before it fetches its missing rows (PCIe, when the fill sources are host memory),
+                                the overlap of transfer and computation that Section 5.2 of the paper is after.  The step still completes on
+                                stream_main                                                                   */
 };
 
 typedef struct qsac_ctx qsac_ctx;

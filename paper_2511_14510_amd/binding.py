@@ -19,7 +19,7 @@ QSAC_F16, QSAC_BF16 = 0, 1
 QSAC_OK, QSAC_EINVAL, QSAC_ENULL, QSAC_ERANGE = 0, -1, -2, -3
 QSAC_EWORKSPACE, QSAC_EHIP, QSAC_ESTATE, QSAC_EALIGN, QSAC_ETIMEOUT = -4, -5, -6, -7, -8
 QSAC_FLAG_DRY_RUN, QSAC_FLAG_SERIAL, QSAC_FLAG_SCORE_VALU, QSAC_FLAG_PROFILE, QSAC_FLAG_FILL_KERNEL = 1, 2, 4, 8, 16
-QSAC_FLAG_PUSH_FILL, QSAC_FLAG_PUSH_HOLD = 32, 64
+QSAC_FLAG_PUSH_FILL, QSAC_FLAG_PUSH_HOLD, QSAC_FLAG_STAGGER = 32, 64, 128
 QSAC_MAX_GROUP, QSAC_MAX_KV_HEADS, QSAC_HEAD_DIM = 8, 64, 128
 
 EXPORTS = ("qsac_workspace_bytes", "qsac_workspace_layout", "qsac_init", "qsac_reset", "qsac_step",

@@ -45,10 +45,14 @@ int check_config(const qsac_config* c) {
   if (c->append_capacity < 0 || c->append_capacity > (1 << 20)) return QSAC_ERANGE;
   if (c->n_sink < 0 || c->n_recent < 0 || (int64_t)c->n_sink + c->n_recent > c->k_max) return QSAC_ERANGE;
   if (c->flags & ~(QSAC_FLAG_DRY_RUN | QSAC_FLAG_SERIAL | QSAC_FLAG_SCORE_VALU | QSAC_FLAG_PROFILE | QSAC_FLAG_FILL_KERNEL |
-                   QSAC_FLAG_PUSH_FILL | QSAC_FLAG_PUSH_HOLD))
+                   QSAC_FLAG_PUSH_FILL | QSAC_FLAG_PUSH_HOLD | QSAC_FLAG_STAGGER))
     return QSAC_EINVAL;
   if ((c->flags & QSAC_FLAG_PUSH_HOLD) && !(c->flags & QSAC_FLAG_PUSH_FILL)) return QSAC_EINVAL;
   if ((c->flags & QSAC_FLAG_PUSH_FILL) && (c->flags & QSAC_FLAG_FILL_KERNEL)) return QSAC_EINVAL;  // one way to fill
+  // the staggered schedule is two plain pull-mode steps on two streams
+  if ((c->flags & QSAC_FLAG_STAGGER) &&
+      ((c->flags & (QSAC_FLAG_SERIAL | QSAC_FLAG_PROFILE | QSAC_FLAG_FILL_KERNEL | QSAC_FLAG_PUSH_FILL)) || c->batch < 2))
+    return QSAC_EINVAL;  // (qsac_init also asks for the second stream)
   if (c->push_threads < 0 || c->push_threads > 64 || c->push_wait_us < 0) return QSAC_ERANGE;
   if (c->q_head_importance)
     for (int i = 0; i < c->n_q_heads; ++i)
@@ -232,6 +236,8 @@ struct PushEngine {
   }
 };
 
+constexpr int kStaggerSlices = 4;  // (2: 3.40 ms, 3 to 8: 3.28 to 3.33 ms, 16: 3.47 ms on the largest workload)
+
 struct qsac_ctx {
   uint32_t magic;
   qsac_config cfg;
@@ -241,7 +247,8 @@ struct qsac_ctx {
   uint64_t steps;
   hipStream_t s_main, s_side;
   hipEvent_t ev_sel, ev_fill;
-  bool dry, overlap, profile, small, fill_kernel;
+  hipEvent_t ev_slice[kStaggerSlices];  // staggered schedule: slice i has finished scoring
+  bool dry, overlap, profile, small, fill_kernel, stagger;
   hipEvent_t prof[kStages + 1];
   double stage_ms[kStages];
   uint64_t stage_calls;
@@ -355,24 +362,24 @@ int drain_profile(qsac_ctx* c) {
 }
 
 template <int DT, int G>
-void launch_score(const qsac_ctx* c, const qsac_step_args* a, u32* keys, u32* hist) {
+void launch_score(const qsac_ctx* c, const qsac_step_args* a, u32* keys, u32* hist, int P, hipStream_t sm) {
   auto q = static_cast<const uint16_t*>(a->q);
   auto K = static_cast<const uint16_t*>(a->K_dev);
   const int64_t N = c->cfg.n_ctx;
   const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
   const bool valu = (c->cfg.flags & QSAC_FLAG_SCORE_VALU) != 0;
   if (c->small) {
-    dim3 grid((unsigned)((N + kScoreRowsSmall - 1) / kScoreRowsSmall), (unsigned)c->P);
+    dim3 grid((unsigned)((N + kScoreRowsSmall - 1) / kScoreRowsSmall), (unsigned)P);
     if (valu)
-      qsac_score_valu_kernel<DT, G, kScoreRowsSmall, false><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
+      qsac_score_valu_kernel<DT, G, kScoreRowsSmall, false><<<grid, 256, 0, sm>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
     else
-      qsac_score_mfma_kernel<DT, G, kScoreRowsSmall, false><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
+      qsac_score_mfma_kernel<DT, G, kScoreRowsSmall, false><<<grid, 256, 0, sm>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
   } else {
-    dim3 grid((unsigned)((N + kScoreRowsLarge - 1) / kScoreRowsLarge), (unsigned)c->P);
+    dim3 grid((unsigned)((N + kScoreRowsLarge - 1) / kScoreRowsLarge), (unsigned)P);
     if (valu)
-      qsac_score_valu_kernel<DT, G, kScoreRowsLarge, true><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
+      qsac_score_valu_kernel<DT, G, kScoreRowsLarge, true><<<grid, 256, 0, sm>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
     else
-      qsac_score_mfma_kernel<DT, G, kScoreRowsLarge, true><<<grid, 256, 0, c->s_main>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
+      qsac_score_mfma_kernel<DT, G, kScoreRowsLarge, true><<<grid, 256, 0, sm>>>(q, K, a->reuse_flags, keys, hist, Hq, Hkv, N, c->L.n_pad, c->cfg.n_sink, c->cfg.n_recent);
   }
 }
 
@@ -406,8 +413,8 @@ AttnArgs attn_args(const qsac_ctx* c, const qsac_step_args* a, const int* fetch_
 }
 
 template <int DT, int G>
-void launch_attn(const qsac_ctx* c, hipStream_t stream, const AttnArgs& A, const FillSrc& src) {
-  dim3 grid((unsigned)A.n_splits, (unsigned)c->P);
+void launch_attn(const qsac_ctx* c, hipStream_t stream, const AttnArgs& A, const FillSrc& src, int P) {
+  dim3 grid((unsigned)A.n_splits, (unsigned)P);
   if (c->fill_kernel || c->push)  // the rows are in their slots before the attention starts
     qsac_attn_kernel<DT, G, false><<<grid, 256, 0, stream>>>(A, src);
   else
@@ -451,12 +458,14 @@ void fill_ctx(qsac_ctx* c, const qsac_config* cfg, const qsac_ws_layout& L) {
   c->overlap = cfg->stream_side != nullptr && cfg->stream_side != cfg->stream_main && !(cfg->flags & QSAC_FLAG_SERIAL);
   c->profile = (cfg->flags & QSAC_FLAG_PROFILE) != 0;
   if (c->profile) c->overlap = false;  // stage times are taken on one stream
+  c->stagger = (cfg->flags & QSAC_FLAG_STAGGER) != 0;
   c->k_bound = 0;
   c->steps = 0;
   c->broken = false;
   c->seen_K_src = c->seen_V_src = nullptr;
   c->K_src_host = c->V_src_host = false;
   c->ev_sel = c->ev_fill = nullptr;
+  for (auto& e : c->ev_slice) e = nullptr;
   c->push = nullptr;
   for (auto& e : c->prof) e = nullptr;
   for (int i = 0; i < kStages; ++i) c->stage_ms[i] = 0.0;
@@ -606,7 +615,45 @@ int push_start(qsac_ctx* c) {
 
 // Enqueues the launches of one step (also what a graph capture records).  QSAC_EHIP if a HIP call fails,
 // possibly after part of the step has been enqueued.
-int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
+// The step arguments of the batch elements from b0 on: every tensor is [B, ...], so a slice of the batch is the
+// same step on offset pointers.
+qsac_step_args slice_args(const qsac_ctx* c, const qsac_step_args* a, int b0) {
+  qsac_step_args s = *a;
+  if (b0 == 0) return s;
+  const size_t Hq = (size_t)c->cfg.n_q_heads, Hkv = (size_t)c->cfg.n_kv_heads, N = (size_t)c->cfg.n_ctx;
+  const size_t k_max = (size_t)c->cfg.k_max, cap = (size_t)c->cfg.append_capacity, b = (size_t)b0, p0 = b * Hkv;
+  auto e16 = [](const void* p, size_t elems) -> const void* {
+    return p ? static_cast<const void*>(static_cast<const uint16_t*>(p) + elems) : nullptr;
+  };
+  s.q = e16(a->q, b * Hq * kD);
+  s.prev_q = const_cast<void*>(e16(a->prev_q, b * Hq * kD));
+  s.K_dev = e16(a->K_dev, p0 * N * kD);
+  s.K_src = e16(a->K_src, p0 * N * kD);
+  s.V_src = e16(a->V_src, p0 * N * kD);
+  s.V_res = e16(a->V_res, b * (size_t)a->n_res * N * kD);
+  s.K_slots = const_cast<void*>(e16(a->K_slots, p0 * k_max * kD));
+  s.V_slots = const_cast<void*>(e16(a->V_slots, p0 * k_max * kD));
+  s.K_app = e16(a->K_app, p0 * cap * kD);
+  s.V_app = e16(a->V_app, p0 * cap * kD);
+  s.slot_idx = a->slot_idx + p0 * k_max;
+  s.out = a->out + b * Hq * kD;
+  s.topk_idx = a->topk_idx + p0 * (size_t)a->k;
+  s.hit_mask = a->hit_mask + p0 * (size_t)a->k;
+  s.reuse_flags = a->reuse_flags + p0;
+  s.sim = a->sim ? a->sim + b * Hq : nullptr;
+  return s;
+}
+
+// What enqueue_range launches: the gate alone, everything after it, or the whole step.
+enum { kGateOnly = 1, kAfterGate = 2, kWholeStep = 3 };
+
+// The step for the batch elements [b0, b0 + nb) on stream sm.  The modes that use both streams inside one range
+// (and the stage timing) apply only to the whole batch on stream_main (`whole`).  after_score: recorded on sm
+// right behind the scoring launch (for a second range that is to start when this one stops loading HBM).
+int enqueue_range(qsac_ctx* c, const qsac_step_args* a_full, int b0, int nb, hipStream_t sm, int what, bool whole,
+                  hipEvent_t after_score) {
+  const qsac_step_args a_slice = slice_args(c, a_full, b0);
+  const qsac_step_args* a = &a_slice;
 
   const qsac_ws_layout& L = c->L;
   char* ws = static_cast<char*>(c->cfg.workspace);
@@ -627,17 +674,39 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
   int* sel_r = reinterpret_cast<int*>(ws + L.sel_r);
   int* fetch_tok = reinterpret_cast<int*>(ws + L.fetch_tok);
 
-  const int P = c->P, G = c->G, k = a->k, k_max = c->cfg.k_max;
+  const int G = c->G, k = a->k, k_max = c->cfg.k_max;
   const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
+  const int P = nb * Hkv;
   const int64_t N = c->cfg.n_ctx;
-  hipStream_t sm = c->s_main;
+  u64* glist = reinterpret_cast<u64*>(bm_new);  // (the list-building select keeps the pairs' lists there)
+  int* chunk_cnt = reinterpret_cast<int*>(ws + L.chunk_cnt);
+  {  // this range's part of every per-pair array of the workspace
+    const size_t p0 = (size_t)b0 * (size_t)Hkv;
+    valid += p0;
+    set_sorted += p0 * (size_t)k_max;
+    keys += p0 * (size_t)L.n_pad;
+    hist += p0 * 3 * kBins;
+    bm_new += p0 * (size_t)L.words;
+    bm_eq += p0 * (size_t)L.words;
+    bm_old += p0 * (size_t)L.words;
+    miss_count += p0;
+    miss_slot += p0 * (size_t)k_max;
+    miss_tok += p0 * (size_t)k_max;
+    part_ml += p0 * (size_t)G * (size_t)L.max_splits * 2;
+    part_acc += p0 * (size_t)G * (size_t)L.max_splits * kD;
+    sel_r += p0 * kSelStride;
+    fetch_tok += p0 * (size_t)k_max;
+    glist += p0 * (size_t)kStreamListCap;
+    chunk_cnt += p0 * (size_t)(L.n_pad / kSelChunk) * 2;
+  }
+  const bool timed = whole && c->profile;
 
-  if (c->profile) {
+  if (timed) {
     int rc = drain_profile(c);
     if (rc != QSAC_OK) return rc;
   }
   auto mark = [&](int i) {
-    if (c->profile) (void)hipEventRecord(c->prof[i], sm);
+    if (timed) (void)hipEventRecord(c->prof[i], sm);
   };
 
   const DevParams* dp = reinterpret_cast<const DevParams*>(a->dev_params);
@@ -654,7 +723,8 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
 
   // 1. gate (+ label update on a miss)
   mark(0);
-  if (c->cfg.dtype == QSAC_F16)
+  if (!(what & kGateOnly)) {
+  } else if (c->cfg.dtype == QSAC_F16)
     qsac_gate_kernel<0><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
                                            a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max,
@@ -664,6 +734,10 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
                                            a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max,
                                            !c->small, dp);
+  if (!(what & kAfterGate)) {
+    HIP_TRY(hipGetLastError());
+    return QSAC_OK;
+  }
   const int rows = attn_rows(P, k + a->n_app);
   const int n_splits = (k + a->n_app + rows - 1) / rows;
   dim3 fill_grid((unsigned)((k + kFillRows - 1) / kFillRows), (unsigned)P);
@@ -673,15 +747,15 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
   };
   auto attend = [&](hipStream_t s, int which) {
     const AttnArgs A = attn_args(c, a, fetch_tok, miss_count, part_ml, part_acc, rows, n_splits, which);
-    QSAC_DISPATCH(launch_attn, c, s, A, src);
+    QSAC_DISPATCH(launch_attn, c, s, A, src, P);
   };
   auto combine = [&]() {
     if (n_splits > 1)
       qsac_combine_kernel<<<P * G, n_splits > 16 ? 512 : 128, 0, sm>>>(part_ml, part_acc, a->reuse_flags, a->out, Hq, Hkv, G, n_splits,
                                                  L.max_splits, 0);
   };
-  const bool side_attn = c->overlap && !c->fill_kernel && !c->push;  // reused heads are attended to beside the select
-  const bool side_fill = c->overlap && c->fill_kernel;               // the fill kernel runs beside their attention
+  const bool side_attn = whole && c->overlap && !c->fill_kernel && !c->push;  // reused heads are attended to beside the select
+  const bool side_fill = whole && c->overlap && c->fill_kernel;               // the fill kernel runs beside their attention
   // push mode: the miss lists go to the host transfer threads, the polling kernel waits for their answer
   u32* push_state = reinterpret_cast<u32*>(ws + L.push);
   auto publish = [&]() {
@@ -694,7 +768,8 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
 
   // 2. scores of the missing pairs
   mark(1);
-  QSAC_DISPATCH(launch_score, c, a, keys, hist);
+  QSAC_DISPATCH(launch_score, c, a, keys, hist, P, sm);
+  if (after_score) HIP_TRY(hipEventRecord(after_score, sm));
   if (side_attn) {
     // The heads that reused need nothing from the miss path.  Their attention starts on the side stream once
     // the scoring pass has had the memory system to itself, and runs beside the select, which is latency
@@ -735,8 +810,7 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
     if (!c->small) {
       // the first bitmap region of the grid-wide path (unused here, sized for this) holds the pairs' lists
       const dim3 grid((unsigned)((N + 4 * kStreamChunkVec * 1024 - 1) / (4 * kStreamChunkVec * 1024)), (unsigned)P);
-      qsac_select_stream_kernel<1024><<<grid, 1024, lds_sel, sm>>>(S, hist, reinterpret_cast<u64*>(bm_new),
-                                                                  kStreamListCap, sel_r, src);
+      qsac_select_stream_kernel<1024><<<grid, 1024, lds_sel, sm>>>(S, hist, glist, kStreamListCap, sel_r, src);
     } else
     switch (vpt) {
       case 2: qsac_select_small_kernel<2, 1024><<<P, 1024, lds_sel, sm>>>(S, src); break;
@@ -751,7 +825,6 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
     if (L.words > 8 * kDiffThreads && k <= kDiffListMax) {
       // Long contexts: the set becomes a token list written by the whole grid, and the one-workgroup diff works on
       // that list in LDS (one workgroup alone takes tens of microseconds to read bitmaps of this size).
-      int* chunk_cnt = reinterpret_cast<int*>(ws + L.chunk_cnt);
       qsac_mark_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, keys, hist, bm_new, bm_eq, bm_old, sel_r, chunk_cnt, N,
                                                 L.n_pad, L.words, k);
       qsac_emit_kernel<<<sel_grid, 256, 0, sm>>>(a->reuse_flags, bm_new, bm_eq, chunk_cnt, sel_r, set_sorted,
@@ -787,7 +860,7 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
     HIP_TRY(hipStreamWaitEvent(sm, c->ev_fill, 0));
     attend(sm, 2);
     combine();
-  } else if (c->push && !c->profile) {
+  } else if (c->push && !timed) {
     // the transfer runs beside the attention of the pairs that reused their cache
     publish();
     attend(sm, 1);
@@ -806,9 +879,31 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
     mark(5);
     combine();
     mark(6);
-    c->prof_pending = c->profile;
+    if (whole) c->prof_pending = c->profile;
   }
   HIP_TRY(hipGetLastError());
+  return QSAC_OK;
+}
+
+// One step.  Staggered schedule (QSAC_FLAG_STAGGER): the gate for everybody, then the batch in up to kStaggerSlices
+// slices that alternate between stream_main and stream_side, each starting when the one before it has finished
+// scoring: a slice scores (HBM) while the slice before it fetches its missing rows (PCIe when the fill sources
+// are host memory), and the link never waits for a scoring pass after the first.
+int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
+  const int B = c->cfg.batch;
+  if (!c->stagger) return enqueue_range(c, a, 0, B, c->s_main, kWholeStep, true, nullptr);
+  int rc = enqueue_range(c, a, 0, B, c->s_main, kGateOnly, false, nullptr);
+  if (rc != QSAC_OK) return rc;
+  const int n = B < kStaggerSlices ? B : kStaggerSlices;
+  for (int i = 0; i < n; ++i) {
+    const int b0 = (int)((int64_t)B * i / n), b1 = (int)((int64_t)B * (i + 1) / n);
+    hipStream_t st = (i & 1) ? c->s_side : c->s_main;
+    if (i > 0) HIP_TRY(hipStreamWaitEvent(st, c->ev_slice[i - 1], 0));  // (also orders the side stream behind the gate)
+    rc = enqueue_range(c, a, b0, b1 - b0, st, kAfterGate, false, i + 1 < n ? c->ev_slice[i] : nullptr);
+    if (rc != QSAC_OK) return rc;
+  }
+  HIP_TRY(hipEventRecord(c->ev_fill, c->s_side));
+  HIP_TRY(hipStreamWaitEvent(c->s_main, c->ev_fill, 0));
   return QSAC_OK;
 }
 
@@ -840,6 +935,8 @@ int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
   make_layout(cfg, &L);
   const bool dry = (cfg->flags & QSAC_FLAG_DRY_RUN) != 0;
   if (!dry) {
+    if ((cfg->flags & QSAC_FLAG_STAGGER) && (cfg->stream_side == nullptr || cfg->stream_side == cfg->stream_main))
+      return QSAC_EINVAL;
     if (!cfg->workspace) return QSAC_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(cfg->workspace) & 255u) return QSAC_EWORKSPACE;
     if (cfg->workspace_bytes < L.total) return QSAC_EWORKSPACE;
@@ -860,6 +957,12 @@ int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
     g_last_hip = (int)hipGetLastError();
     return fail(QSAC_EHIP);
   }
+  if (c->stagger)
+    for (auto& e : c->ev_slice)
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+        g_last_hip = (int)hipGetLastError();
+        return fail(QSAC_EHIP);
+      }
   if (c->profile)
     for (auto& e : c->prof)
       if (hipEventCreate(&e) != hipSuccess) {
@@ -1012,7 +1115,7 @@ int qsac_step_static(const qsac_config* cfg, const qsac_step_args* a, int reset)
   int rc = check_config(cfg);
   if (rc != QSAC_OK) return rc;
   if (cfg->flags & ~(QSAC_FLAG_SCORE_VALU | QSAC_FLAG_FILL_KERNEL)) return QSAC_EINVAL;
-  if (cfg->stream_side) return QSAC_EINVAL;
+  if (cfg->stream_side || (cfg->flags & QSAC_FLAG_STAGGER)) return QSAC_EINVAL;
   qsac_ws_layout L;
   make_layout(cfg, &L);
   if (L.total > (size_t)QSAC_STATIC_SCRATCH_BYTES) return QSAC_EWORKSPACE;
@@ -1113,6 +1216,8 @@ int qsac_free(qsac_ctx* c) {
   if (!c->dry) {
     if (c->ev_sel) (void)hipEventDestroy(c->ev_sel);
     if (c->ev_fill) (void)hipEventDestroy(c->ev_fill);
+    for (auto& e : c->ev_slice)
+      if (e) (void)hipEventDestroy(e);
     for (auto& e : c->prof)
       if (e) (void)hipEventDestroy(e);
   }

@@ -84,6 +84,10 @@ def test_workspace_size_and_layout(lib):
     (dict(flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_PUSH_FILL | Q.QSAC_FLAG_FILL_KERNEL), Q.QSAC_EINVAL),  # two ways to fill
     (dict(flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_PUSH_FILL, push_threads=65), Q.QSAC_ERANGE),
     (dict(flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_PUSH_FILL, push_wait_us=-1), Q.QSAC_ERANGE),
+    (dict(flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_STAGGER), Q.QSAC_EINVAL),                           # a batch of one has no halves
+    (dict(B=2, flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_STAGGER | Q.QSAC_FLAG_FILL_KERNEL), Q.QSAC_EINVAL),
+    (dict(B=2, flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_STAGGER | Q.QSAC_FLAG_PUSH_FILL), Q.QSAC_EINVAL),
+    (dict(B=2, flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_STAGGER | Q.QSAC_FLAG_PROFILE), Q.QSAC_EINVAL),
 ])
 def test_bad_configs_are_rejected(lib, kw, code):
     a = dict(B=1, Hq=8, Hkv=2, N=4096, k_max=256, dtype=Q.QSAC_F16, flags=Q.QSAC_FLAG_DRY_RUN, importance=None, D=128,
@@ -96,6 +100,14 @@ def test_bad_configs_are_rejected(lib, kw, code):
     ctx = C.c_void_p()
     assert lib.qsac_init(C.byref(cfg), C.byref(ctx)) == code
     assert not ctx.value
+
+
+def test_staggered_schedule_needs_a_second_stream(lib):
+    """Checked by qsac_init before it touches a device (the workspace size does not depend on streams)."""
+    cfg = Q.make_config(2, 8, 2, 4096, 256, Q.QSAC_F16, Q.QSAC_FLAG_STAGGER, None)
+    assert Q.qsac_workspace_bytes(cfg) > 0
+    ctx = C.c_void_p()
+    assert lib.qsac_init(C.byref(cfg), C.byref(ctx)) == Q.QSAC_EINVAL and not ctx.value
 
 
 def test_workspace_checks_without_dry_run(lib):

@@ -80,3 +80,12 @@ def test_low_sim_stress_full_size():
         rates.append(st["reuse_heads"] / (st["reuse_heads"] + st["miss_heads"]))
         assert st["bytes_filled_host"] == 512 * st["slot_misses"]
     assert rates[0] > rates[1] >= rates[2] > 0, rates     # four steps tell 0.9 from 0.95 only by a few pairs
+
+
+def test_low_sim_stress_full_size_staggered_schedule():
+    """The largest workload under QSAC_FLAG_STAGGER (what bench.py's headline line runs): four slices of eight
+    batch elements on two streams; every pair on the first step, a sample afterwards."""
+    [(par, st)], w = run_full("low_sim_stress", steps=3, n_sample=16, flags=Q.QSAC_FLAG_STAGGER, side_stream=True,
+                              all_last=False)
+    assert par.n_reuse > 0 and par.n_miss > w.P
+    assert st["bytes_filled_host"] == 512 * st["slot_misses"]

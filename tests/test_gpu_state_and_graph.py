@@ -96,6 +96,60 @@ def test_graph_replay_matches_eager_and_the_oracle(H, N, k, flags, side):
     sess.close()
 
 
+@pytest.mark.parametrize("N,k,host,dtype", [(6000, 300, True, "bf16"), (33000, 1000, True, "f16"),
+                                            (70001, 500, False, "bf16"), (140001, 400, True, "bf16")])
+def test_staggered_schedule_matches_the_oracle(H, N, k, host, dtype):
+    """QSAC_FLAG_STAGGER: the two halves of the batch (1 + 2 elements here) run on two streams, the second half
+    scoring while the first fetches its rows; every select path, rows from pinned host memory or HBM."""
+    B, Hq, Hkv = 3, 8, 2
+    print(f"staggered case N={N} k={k} host={host} {dtype}", flush=True)
+    sess, Kb, Ksb, Vsb = H.make_session(B, Hq, Hkv, N, k + 5, dtype, 91, host, host, Q.QSAC_FLAG_STAGGER, None, True)
+    par = H.Parity(sess, dtype, Kb, Ksb, Vsb)
+    chain = W.QueryChain(B, Hq, 128, 0.95, 91)
+    for t in range(10):
+        par.step(chain.next(), 0.9, k, label=f"staggered step {t}")
+    assert par.n_reuse > 0 and par.n_miss > B * Hkv
+    st = sess.stats()
+    assert st["reuse_heads"] == par.n_reuse and st["miss_heads"] == par.n_miss
+    sess.close()
+
+
+def test_staggered_schedule_replays_from_a_graph(H):
+    """The staggered step forks to stream_side and joins again inside one capture; replays equal eager steps."""
+    B, Hq, Hkv, N, k, steps = 4, 8, 2, 9000, 256, 16
+    K, V = W.make_kv(B, Hkv, N, 128, "bf16", 93)
+    chain = W.QueryChain(B, Hq, 128, 0.95, 93)
+    qs = [W.round_to(chain.next(), "bf16").cuda() for _ in range(steps)]
+    taus = [[0.9, 0.85]] * steps
+
+    def session():
+        return Q.Session(B, Hq, Hkv, N, k, "bf16", K.cuda(), K.cuda(), V.pin_memory(), flags=Q.QSAC_FLAG_STAGGER,
+                         side_stream=True)
+
+    eager = session()
+    ref = []
+    for t in range(steps):
+        eager.step(qs[t], taus[t], k)
+        eager.sync()
+        ref.append(_snapshot(eager))
+    eager.close()
+    sess = session()
+    q_buf = torch.zeros((B, Hq, 128), dtype=torch.bfloat16, device="cuda:0")
+    table = sess.dev_params_table(taus, [0] * steps)
+    dp = torch.zeros(C.sizeof(Q.qsac_dev_params), dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    graph = Q.qsac_graph_capture(sess.ctx, sess.step_args(q_buf, None, k, dev_params=dp, n_app_bound=0))
+    for t in range(steps):
+        sess.copy_on_main(q_buf, qs[t])
+        sess.copy_on_main(dp, table[t])
+        Q.qsac_graph_launch(graph)
+        sess.sync()
+        for got, want in zip(_snapshot(sess), ref[t]):
+            assert torch.equal(got, want), f"replay {t} differs from the eager step"
+    Q.qsac_graph_free(graph)
+    sess.close()
+
+
 def test_checkpoint_and_resume(H):
     """The cache state is the caller's slot tensors, slot table and labels plus the library's workspace
     (validity flags, the sorted set of every head): 64 steps in one go equal 32 steps, a copy of that state
