@@ -245,22 +245,7 @@ __device__ __forceinline__ int wave_totals_exclusive(int wave_value, int* s_wave
   return below_and_total<NW>(s_wave, total);
 }
 
-// The same for two values per wave at once.
-template <int NW>
-__device__ __forceinline__ void wave_totals_exclusive2(int va, int vb, int* s_wave2 /*[2*NW]*/, int* base_a,
-                                                       int* base_b) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  __syncthreads();
-  if (lane == 0) {
-    s_wave2[wave] = va;
-    s_wave2[NW + wave] = vb;
-  }
-  __syncthreads();
-  *base_a = below_and_total<NW>(s_wave2, nullptr);
-  *base_b = below_and_total<NW>(s_wave2 + NW, nullptr);
-}
-
-// The same for three values per wave at once; *total_c gets the sum of the third.
+// The same for three values per wave at once (s_wave3: 3 * NW ints); *total_c gets the sum of the third.
 // LEAD = false: a barrier already separates the call from the last use of s_wave3.
 template <int NW, bool LEAD = true>
 __device__ __forceinline__ void wave_totals_exclusive3(int va, int vb, int vc, int* s_wave3 /*[3*NW]*/, int* base_a,
