@@ -236,11 +236,11 @@ class Bench:
         }
         res["_w"], res["_tau"] = w, tau
         if not single and (w.host_k or w.host_v) and w.B >= 2 and (detail == "headline" or name == "qwen25_14b_128k_offload"):
-            # the same steps under the staggered schedule: batch slices alternate between two streams, a slice scores
-            # (HBM) while the slice before it fetches its rows (PCIe)
+            # the same steps under the staggered schedule: batch slices pipelined over two streams, a slice is scored
+            # (HBM) while the rows of the slice before it are fetched (PCIe)
             t_st, d_st = timed(Q.QSAC_FLAG_STAGGER, side=True)
             res["staggered"] = {"steps_per_s": K_steps / t_st, "ms_per_step": 1e3 * t_st / K_steps,
-                                "plain_ms_per_step": res["ms_per_step"], "slices": min(w.B, 4),
+                                "plain_ms_per_step": res["ms_per_step"], "slices": stagger_slices(w.B),
                                 "host_GBps_over_the_step": d_st["bytes_filled_host"] / t_st / 1e9}
         if single:
             res["_cfg_extra"] = {}
@@ -416,6 +416,17 @@ class Bench:
                           f"pairs, rate scaled by {n_pairs}/{w.P}), after an untimed all-miss first step ({first:.2f} s)"}
 
 
+def stagger_slices(B):
+    """Batch elements per slice of the library's staggered schedule (enqueue_step in csrc/qsac.hip): B / 8 first,
+    then each about one and a half times the one before; a small rest joins the last slice."""
+    sizes, at, size = [], 0, max(B // 8, 1)
+    while at < B:
+        nxt = B if (len(sizes) + 1 == 8 or B - at - size < size // 2) else at + size
+        sizes.append(nxt - at)
+        at, size = nxt, max(size + 1, size * 3 // 2)
+    return sizes
+
+
 def config_of(res, Q, a):
     w, tau = res["_w"], res["_tau"]
     cfg = {"workload": w.name, "batch": w.B, "n_q_heads": w.Hq, "n_kv_heads": w.Hkv, "head_dim": w.D,
@@ -503,7 +514,7 @@ def brief(res):
     if "graph" in res:
         o["graph"] = {k: r4(v) for k, v in res["graph"].items()}
     if "staggered" in res:
-        o["staggered"] = {k: r4(v) for k, v in res["staggered"].items()}
+        o["staggered"] = {k: (v if k == "slices" else r4(v)) for k, v in res["staggered"].items()}
     if "cpu_baseline" in res:
         c = res["cpu_baseline"]
         o["oracle"] = {"steps_per_s": r4(c["value"]), "cores": c["cores"]}
@@ -558,13 +569,14 @@ def main():
     if "staggered" in head:
         st = head["staggered"]
         line["schedules"] = {"plain": {"steps_per_s": r4(head["steps_per_s"]), "ms_per_step": r4(head["ms_per_step"])},
-                             "staggered": {k: r4(v) for k, v in st.items()}}
+                             "staggered": {k: (v if k == "slices" else r4(v)) for k, v in st.items()}}
         if st["steps_per_s"] > head["steps_per_s"]:
             # the headline is the faster of the two schedules; the stage times and rooflines below are taken kernel by
             # kernel on one stream (the plain schedule), where each kernel has the machine to itself
             line["value"], line["ms_per_step"] = st["steps_per_s"], st["ms_per_step"]
-            line["config"]["schedule"] = ("staggered (QSAC_FLAG_STAGGER): %d batch slices alternate between two streams, "
-                                          "a slice scores while the slice before it fetches its rows" % st["slices"])
+            line["config"]["schedule"] = ("staggered (QSAC_FLAG_STAGGER): batch slices of %s elements pipelined over two "
+                                          "streams, a slice is scored while the rows of the slice before it are fetched"
+                                          % "+".join(str(x) for x in st["slices"]))
     if "hbm" in head:
         rf = rooflines(head)
         # dominant kernel: the attention kernel fetching the missing rows over PCIe where the workload offloads,

@@ -87,14 +87,17 @@ enum {
                                 on the context returns QSAC_ETIMEOUT until qsac_reset                         */
   QSAC_FLAG_PUSH_HOLD = 64,  /* test aid for push mode: the transfer threads ignore every request, so every polling
                                 kernel runs into its bound                                                  */
-  QSAC_FLAG_STAGGER = 128    /* staggered schedule (needs stream_side and batch >= 2; not with SERIAL, PROFILE,
-                                FILL_KERNEL or PUSH_FILL): after the gate, the batch runs in up to four slices
-                                that alternate between stream_main and stream_side, each starting when the one
-                                before it has finished scoring.  The slices are independent (Algorithm 1 is per
-                                head), so the results are those of the plain schedule up to the summation order of
-                                the attention splits; what changes is that a slice scores (HBM) while the slice
-                                before it fetches its missing rows (PCIe, when the fill sources are host memory),
-                                the overlap of transfer and computation that Section 5.2 of the paper is after.  The step still completes on
+  QSAC_FLAG_STAGGER = 128    /* staggered schedule (needs stream_side, batch >= 2 and batch * n_kv_heads <= 8192;
+                                not with SERIAL, PROFILE, FILL_KERNEL or PUSH_FILL): after the gate, the batch runs
+                                in a few slices of growing size, pipelined over the two streams: stream_main scores
+                                and selects slice i + 1 and then attends to slice i, stream_side copies slice i's
+                                missing rows into their slots as soon as its select is through, with a kernel that
+                                keeps only as many reads in flight as the link needs.  The slices are independent
+                                (Algorithm 1 is per head), so the results are those of the plain schedule up to the
+                                summation order of the attention splits; what changes is that a slice is scored
+                                (HBM) while the rows of the slice before it are fetched (PCIe, when the fill sources
+                                are host memory): the overlap of transfer and computation, by a transfer engine of
+                                its own, that Sections 5.2 and 6.2 of the paper are after.  The step still completes on
                                 stream_main                                                                   */
 };
 

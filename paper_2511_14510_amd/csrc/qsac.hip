@@ -51,7 +51,8 @@ int check_config(const qsac_config* c) {
   if ((c->flags & QSAC_FLAG_PUSH_FILL) && (c->flags & QSAC_FLAG_FILL_KERNEL)) return QSAC_EINVAL;  // one way to fill
   // the staggered schedule is two plain pull-mode steps on two streams
   if ((c->flags & QSAC_FLAG_STAGGER) &&
-      ((c->flags & (QSAC_FLAG_SERIAL | QSAC_FLAG_PROFILE | QSAC_FLAG_FILL_KERNEL | QSAC_FLAG_PUSH_FILL)) || c->batch < 2))
+      ((c->flags & (QSAC_FLAG_SERIAL | QSAC_FLAG_PROFILE | QSAC_FLAG_FILL_KERNEL | QSAC_FLAG_PUSH_FILL)) || c->batch < 2 ||
+       (int64_t)c->batch * c->n_kv_heads > 8192))  // (its fill kernel keeps a table of the slice's pairs in LDS)
     return QSAC_EINVAL;  // (qsac_init also asks for the second stream)
   if (c->push_threads < 0 || c->push_threads > 64 || c->push_wait_us < 0) return QSAC_ERANGE;
   if (c->q_head_importance)
@@ -236,7 +237,9 @@ struct PushEngine {
   }
 };
 
-constexpr int kStaggerSlices = 4;  // (2: 3.40 ms, 3 to 8: 3.28 to 3.33 ms, 16: 3.47 ms on the largest workload)
+constexpr int kStaggerSlices = 8;        // at most (a batch of 32 runs as 4 + 6 + 9 + 13)
+constexpr int kTrickleWorkgroups = 96;  // of the staggered schedule's fill kernel (32: 3.40 ms, 64: 3.31 to 3.34,
+                                        // 96: 3.25, 128: 3.26, 256: 3.73 per step of the largest workload, 4 slices)
 
 struct qsac_ctx {
   uint32_t magic;
@@ -247,7 +250,7 @@ struct qsac_ctx {
   uint64_t steps;
   hipStream_t s_main, s_side;
   hipEvent_t ev_sel, ev_fill;
-  hipEvent_t ev_slice[kStaggerSlices];  // staggered schedule: slice i has finished scoring
+  hipEvent_t ev_selected[kStaggerSlices], ev_filled[kStaggerSlices];  // staggered schedule, per batch slice
   bool dry, overlap, profile, small, fill_kernel, stagger;
   hipEvent_t prof[kStages + 1];
   double stage_ms[kStages];
@@ -413,9 +416,9 @@ AttnArgs attn_args(const qsac_ctx* c, const qsac_step_args* a, const int* fetch_
 }
 
 template <int DT, int G>
-void launch_attn(const qsac_ctx* c, hipStream_t stream, const AttnArgs& A, const FillSrc& src, int P) {
+void launch_attn(const qsac_ctx* c, hipStream_t stream, const AttnArgs& A, const FillSrc& src, int P, bool filled) {
   dim3 grid((unsigned)A.n_splits, (unsigned)P);
-  if (c->fill_kernel || c->push)  // the rows are in their slots before the attention starts
+  if (filled || c->fill_kernel || c->push)  // the rows are in their slots before the attention starts
     qsac_attn_kernel<DT, G, false><<<grid, 256, 0, stream>>>(A, src);
   else
     qsac_attn_kernel<DT, G, true><<<grid, 256, 0, stream>>>(A, src);
@@ -465,7 +468,8 @@ void fill_ctx(qsac_ctx* c, const qsac_config* cfg, const qsac_ws_layout& L) {
   c->seen_K_src = c->seen_V_src = nullptr;
   c->K_src_host = c->V_src_host = false;
   c->ev_sel = c->ev_fill = nullptr;
-  for (auto& e : c->ev_slice) e = nullptr;
+  for (auto& e : c->ev_selected) e = nullptr;
+  for (auto& e : c->ev_filled) e = nullptr;
   c->push = nullptr;
   for (auto& e : c->prof) e = nullptr;
   for (int i = 0; i < kStages; ++i) c->stage_ms[i] = 0.0;
@@ -644,14 +648,14 @@ qsac_step_args slice_args(const qsac_ctx* c, const qsac_step_args* a, int b0) {
   return s;
 }
 
-// What enqueue_range launches: the gate alone, everything after it, or the whole step.
-enum { kGateOnly = 1, kAfterGate = 2, kWholeStep = 3 };
+// What enqueue_range launches.  The whole step is gate, scoring + select (with the diff), and attention with
+// the fill folded in or before it, as the context says; the staggered schedule asks for the pieces one by one,
+// with the fill as the trickle kernel and the attention over slots that are already filled.
+enum { kGate = 1, kScoreSelect = 2, kAttend = 4, kWholeStep = 7, kTrickleFill = 8, kAttendFilled = 16 };
 
 // The step for the batch elements [b0, b0 + nb) on stream sm.  The modes that use both streams inside one range
-// (and the stage timing) apply only to the whole batch on stream_main (`whole`).  after_score: recorded on sm
-// right behind the scoring launch (for a second range that is to start when this one stops loading HBM).
-int enqueue_range(qsac_ctx* c, const qsac_step_args* a_full, int b0, int nb, hipStream_t sm, int what, bool whole,
-                  hipEvent_t after_score) {
+// (and the stage timing) apply only to the whole batch on stream_main (`whole`).
+int enqueue_range(qsac_ctx* c, const qsac_step_args* a_full, int b0, int nb, hipStream_t sm, int what, bool whole) {
   const qsac_step_args a_slice = slice_args(c, a_full, b0);
   const qsac_step_args* a = &a_slice;
 
@@ -723,7 +727,7 @@ int enqueue_range(qsac_ctx* c, const qsac_step_args* a_full, int b0, int nb, hip
 
   // 1. gate (+ label update on a miss)
   mark(0);
-  if (!(what & kGateOnly)) {
+  if (!(what & kGate)) {
   } else if (c->cfg.dtype == QSAC_F16)
     qsac_gate_kernel<0><<<P, 256, 0, sm>>>(static_cast<const uint16_t*>(a->q), static_cast<uint16_t*>(a->prev_q),
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
@@ -734,7 +738,7 @@ int enqueue_range(qsac_ctx* c, const qsac_step_args* a_full, int b0, int nb, hip
                                            importance, tau, valid, set_sorted, a->topk_idx, a->hit_mask,
                                            a->reuse_flags, a->sim, miss_count, hist, stats, Hq, Hkv, G, k, k_max,
                                            !c->small, dp);
-  if (!(what & kAfterGate)) {
+  if (!(what & ~kGate)) {
     HIP_TRY(hipGetLastError());
     return QSAC_OK;
   }
@@ -747,7 +751,7 @@ int enqueue_range(qsac_ctx* c, const qsac_step_args* a_full, int b0, int nb, hip
   };
   auto attend = [&](hipStream_t s, int which) {
     const AttnArgs A = attn_args(c, a, fetch_tok, miss_count, part_ml, part_acc, rows, n_splits, which);
-    QSAC_DISPATCH(launch_attn, c, s, A, src, P);
+    QSAC_DISPATCH(launch_attn, c, s, A, src, P, (what & kAttendFilled) != 0);
   };
   auto combine = [&]() {
     if (n_splits > 1)
@@ -768,8 +772,7 @@ int enqueue_range(qsac_ctx* c, const qsac_step_args* a_full, int b0, int nb, hip
 
   // 2. scores of the missing pairs
   mark(1);
-  QSAC_DISPATCH(launch_score, c, a, keys, hist, P, sm);
-  if (after_score) HIP_TRY(hipEventRecord(after_score, sm));
+  if (what & kScoreSelect) QSAC_DISPATCH(launch_score, c, a, keys, hist, P, sm);
   if (side_attn) {
     // The heads that reused need nothing from the miss path.  Their attention starts on the side stream once
     // the scoring pass has had the memory system to itself, and runs beside the select, which is latency
@@ -781,7 +784,8 @@ int enqueue_range(qsac_ctx* c, const qsac_step_args* a_full, int b0, int nb, hip
   }
   // 3. select the k best, diff against the cache slots
   mark(2);
-  if (N <= kStreamMaxN) {
+  if (!(what & kScoreSelect)) {
+  } else if (N <= kStreamMaxN) {
     // one workgroup per pair: the keys in its registers (vpt key vectors per thread), or streamed
     const int64_t nvec = (N + 3) / 4;
     const int vpt = nvec <= 2 * kDiffThreads ? 2 : nvec <= 4 * kDiffThreads ? 4 : nvec <= 8 * kDiffThreads ? 8 : 16;
@@ -845,6 +849,18 @@ int enqueue_range(qsac_ctx* c, const qsac_step_args* a_full, int b0, int nb, hip
 #undef QSAC_DIFF
     }
   }
+  if (what & kTrickleFill)
+    qsac_fill_trickle_kernel<<<kTrickleWorkgroups, 256, (size_t)(P + 1) * sizeof(int), sm>>>(miss_count, miss_slot, miss_tok, src,
+                                                               static_cast<v4u*>(a->K_slots),
+                                                               static_cast<v4u*>(a->V_slots), Hkv, N, k_max, P);
+  if (what & kAttendFilled) {
+    attend(sm, 0);
+    combine();
+  }
+  if (!(what & kAttend)) {
+    HIP_TRY(hipGetLastError());
+    return QSAC_OK;
+  }
   // 4. fill the missing rows (own kernel, or folded into the attention kernel's loads); 5. attention
   if (side_attn) {
     attend(sm, 2);
@@ -885,25 +901,44 @@ int enqueue_range(qsac_ctx* c, const qsac_step_args* a_full, int b0, int nb, hip
   return QSAC_OK;
 }
 
-// One step.  Staggered schedule (QSAC_FLAG_STAGGER): the gate for everybody, then the batch in up to kStaggerSlices
-// slices that alternate between stream_main and stream_side, each starting when the one before it has finished
-// scoring: a slice scores (HBM) while the slice before it fetches its missing rows (PCIe when the fill sources
-// are host memory), and the link never waits for a scoring pass after the first.
+// One step.  Staggered schedule (QSAC_FLAG_STAGGER): the gate for everybody, then the batch in up to
+// kStaggerSlices slices, software-pipelined over the two streams: stream_main scores and selects slice i + 1,
+// then attends to slice i; stream_side fills slice i's missing rows (trickle kernel) as soon as its select is
+// through.  So the fetch of one slice (PCIe when the fill sources are host memory) runs beside the scoring of the
+// next (HBM), the link waits for a scoring pass only once, at the start, and stream_side is joined back with the
+// last slice's fill.
 int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
   const int B = c->cfg.batch;
-  if (!c->stagger) return enqueue_range(c, a, 0, B, c->s_main, kWholeStep, true, nullptr);
-  int rc = enqueue_range(c, a, 0, B, c->s_main, kGateOnly, false, nullptr);
+  if (!c->stagger) return enqueue_range(c, a, 0, B, c->s_main, kWholeStep, true);
+  int rc = enqueue_range(c, a, 0, B, c->s_main, kGate, false);
   if (rc != QSAC_OK) return rc;
-  const int n = B < kStaggerSlices ? B : kStaggerSlices;
-  for (int i = 0; i < n; ++i) {
-    const int b0 = (int)((int64_t)B * i / n), b1 = (int)((int64_t)B * (i + 1) / n);
-    hipStream_t st = (i & 1) ? c->s_side : c->s_main;
-    if (i > 0) HIP_TRY(hipStreamWaitEvent(st, c->ev_slice[i - 1], 0));  // (also orders the side stream behind the gate)
-    rc = enqueue_range(c, a, b0, b1 - b0, st, kAfterGate, false, i + 1 < n ? c->ev_slice[i] : nullptr);
-    if (rc != QSAC_OK) return rc;
+  // Slice sizes: a small first slice, so that the link starts early, then each about one and a half times the one
+  // before: beside the fill a scoring pass runs at about a third of its speed, and the scoring of slice i + 1 has
+  // to be through before the fill of slice i is.
+  int start[kStaggerSlices + 1];
+  int n = 0;
+  for (int at = 0, size = B / 8 > 0 ? B / 8 : 1; at < B; size = size + 1 > size * 3 / 2 ? size + 1 : size * 3 / 2) {
+    start[n++] = at;
+    at = (n == kStaggerSlices || B - at - size < size / 2) ? B : at + size;  // (a small rest joins the last slice)
   }
-  HIP_TRY(hipEventRecord(c->ev_fill, c->s_side));
-  HIP_TRY(hipStreamWaitEvent(c->s_main, c->ev_fill, 0));
+  start[n] = B;
+  auto lo = [&](int i) { return start[i]; };
+  for (int i = 0; i <= n; ++i) {
+    if (i < n) {
+      rc = enqueue_range(c, a, lo(i), lo(i + 1) - lo(i), c->s_main, kScoreSelect, false);
+      if (rc != QSAC_OK) return rc;
+      HIP_TRY(hipEventRecord(c->ev_selected[i], c->s_main));
+      HIP_TRY(hipStreamWaitEvent(c->s_side, c->ev_selected[i], 0));
+      rc = enqueue_range(c, a, lo(i), lo(i + 1) - lo(i), c->s_side, kTrickleFill, false);
+      if (rc != QSAC_OK) return rc;
+      HIP_TRY(hipEventRecord(c->ev_filled[i], c->s_side));
+    }
+    if (i > 0) {
+      HIP_TRY(hipStreamWaitEvent(c->s_main, c->ev_filled[i - 1], 0));
+      rc = enqueue_range(c, a, lo(i - 1), lo(i) - lo(i - 1), c->s_main, kAttendFilled, false);
+      if (rc != QSAC_OK) return rc;
+    }
+  }
   return QSAC_OK;
 }
 
@@ -958,8 +993,9 @@ int qsac_init(const qsac_config* cfg, qsac_ctx** out) {
     return fail(QSAC_EHIP);
   }
   if (c->stagger)
-    for (auto& e : c->ev_slice)
-      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+    for (int i = 0; i < 2 * kStaggerSlices; ++i)
+      if (hipEventCreateWithFlags(i < kStaggerSlices ? &c->ev_selected[i] : &c->ev_filled[i - kStaggerSlices],
+                                  hipEventDisableTiming) != hipSuccess) {
         g_last_hip = (int)hipGetLastError();
         return fail(QSAC_EHIP);
       }
@@ -1216,7 +1252,9 @@ int qsac_free(qsac_ctx* c) {
   if (!c->dry) {
     if (c->ev_sel) (void)hipEventDestroy(c->ev_sel);
     if (c->ev_fill) (void)hipEventDestroy(c->ev_fill);
-    for (auto& e : c->ev_slice)
+    for (auto& e : c->ev_selected)
+      if (e) (void)hipEventDestroy(e);
+    for (auto& e : c->ev_filled)
       if (e) (void)hipEventDestroy(e);
     for (auto& e : c->prof)
       if (e) (void)hipEventDestroy(e);

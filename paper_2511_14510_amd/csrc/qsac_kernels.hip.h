@@ -1835,6 +1835,68 @@ __global__ __launch_bounds__(256) void qsac_fill_kernel(const int* __restrict__ 
     }
 }
 
+// The same copy for the staggered schedule, where it runs on the second stream beside the scoring of the next
+// batch slice: a small, fixed number of workgroups (the grid) walks the miss lists of all P pairs of a slice laid
+// end to end, a 16-lane group per row, two rows of K and V (four 16-byte loads) in flight per lane.  That is all a PCIe link
+// needs to stay full (measured: 16 workgroups with two loads per lane in flight read pinned memory at 57 GB/s), and
+// it matters that it is no more: host reads wait microseconds in the queues they share with everybody's HBM reads,
+// and a kernel that keeps tens of MiB of them in flight slows an HBM stream beside it tenfold and more (a 512-MiB
+// read: 79 us alone, 110 us beside 16 such workgroups, 4.2 ms beside 2048 with eight loads per lane).
+__global__ __launch_bounds__(256) void qsac_fill_trickle_kernel(const int* __restrict__ miss_count,
+                                                                const int* __restrict__ miss_slot,
+                                                                const int* __restrict__ miss_tok, FillSrc src,
+                                                                v4u* __restrict__ K_slots, v4u* __restrict__ V_slots,
+                                                                int Hkv, int64_t N, int k_max, int P) {
+  // The miss lists of the P pairs laid end to end: s_pre[p] rows come before pair p's.  Every workgroup builds the
+  // same table (P ints of dynamic LDS, plus one) and takes every gridDim.x-th run of 32 rows.
+  extern __shared__ int s_pre[];
+  for (int p = threadIdx.x; p < P; p += 256) s_pre[p + 1] = miss_count[p];
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    s_pre[0] = 0;
+    for (int p = 1; p <= P; ++p) {
+      run += s_pre[p];
+      s_pre[p] = run;
+    }
+  }
+  __syncthreads();
+  const int R = s_pre[P];
+  const int c = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int stride = (int)gridDim.x * 32;
+  int pp[2] = {0, 0};  // the pair a row belongs to only ever moves forward
+  for (int r0 = (int)blockIdx.x * 32 + grp; r0 < R; r0 += stride) {
+    int slot[2];
+    v4u kr[2], vr[2];
+    v4u *Kd[2], *Vd[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int r = r0 + u * 16;
+      slot[u] = -1;
+      if (r < R) {
+        int p = pp[u];
+        while (r >= s_pre[p + 1]) ++p;
+        pp[u] = p;
+        const int e = r - s_pre[p];
+        slot[u] = miss_slot[(size_t)p * k_max + e];
+        const size_t tok = (size_t)miss_tok[(size_t)p * k_max + e];
+        const v4u *Ks, *Vs;
+        fill_rows_of(src, p, Hkv, N, Ks, Vs);
+        kr[u] = Ks[tok * kRowU4 + c];
+        vr[u] = Vs[tok * kRowU4 + c];
+        Kd[u] = K_slots + ((size_t)p * k_max + slot[u]) * kRowU4;
+        Vd[u] = V_slots + ((size_t)p * k_max + slot[u]) * kRowU4;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      if (slot[u] >= 0) {
+        Kd[u][c] = kr[u];
+        Vd[u][c] = vr[u];
+      }
+  }
+}
+
 // ---------------------------------------------------------------- push-mode transfer
 
 // Push mode (Section 5.2 of the paper, GPU-centric synchronization; Section 6.2, zero-copy transfer engine): the
