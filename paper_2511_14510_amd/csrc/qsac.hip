@@ -238,8 +238,8 @@ struct PushEngine {
 };
 
 constexpr int kStaggerSlices = 8;        // at most (a batch of 32 runs as 4 + 6 + 9 + 13)
-constexpr int kTrickleWorkgroups = 96;  // of the staggered schedule's fill kernel (32: 3.40 ms, 64: 3.31 to 3.34,
-                                        // 96: 3.25, 128: 3.26, 256: 3.73 per step of the largest workload, 4 slices)
+constexpr int kTrickleWorkgroups = 64;  // of the staggered schedule's fill kernel (32: 3.32 ms, 48: 3.16, 64: 3.14,
+                                        // 96: 3.23, 128: 3.19 per step of the largest workload)
 
 struct qsac_ctx {
   uint32_t magic;

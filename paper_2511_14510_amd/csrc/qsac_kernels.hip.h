@@ -1865,34 +1865,44 @@ __global__ __launch_bounds__(256) void qsac_fill_trickle_kernel(const int* __res
   const int c = threadIdx.x & 15, grp = threadIdx.x >> 4;
   const int stride = (int)gridDim.x * 32;
   int pp[2] = {0, 0};  // the pair a row belongs to only ever moves forward
-  for (int r0 = (int)blockIdx.x * 32 + grp; r0 < R; r0 += stride) {
-    int slot[2];
-    v4u kr[2], vr[2];
-    v4u *Kd[2], *Vd[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int r = r0 + u * 16;
-      slot[u] = -1;
-      if (r < R) {
-        int p = pp[u];
-        while (r >= s_pre[p + 1]) ++p;
-        pp[u] = p;
-        const int e = r - s_pre[p];
-        slot[u] = miss_slot[(size_t)p * k_max + e];
-        const size_t tok = (size_t)miss_tok[(size_t)p * k_max + e];
-        const v4u *Ks, *Vs;
-        fill_rows_of(src, p, Hkv, N, Ks, Vs);
-        kr[u] = Ks[tok * kRowU4 + c];
-        vr[u] = Vs[tok * kRowU4 + c];
-        Kd[u] = K_slots + ((size_t)p * k_max + slot[u]) * kRowU4;
-        Vd[u] = V_slots + ((size_t)p * k_max + slot[u]) * kRowU4;
-      }
+  // entry of row r (pair, slot, token); the list entries of the next round are requested while this round's rows
+  // are on their way, so that a round costs one trip over the link, not a trip to the lists and then one
+  struct Entry {
+    int p, slot, tok;
+  };
+  auto entry = [&](int r, int u) {
+    Entry en = {0, -1, 0};
+    if (r < R) {
+      int p = pp[u];
+      while (r >= s_pre[p + 1]) ++p;
+      pp[u] = p;
+      const int e = r - s_pre[p];
+      en.p = p;
+      en.slot = miss_slot[(size_t)p * k_max + e];
+      en.tok = miss_tok[(size_t)p * k_max + e];
     }
+    return en;
+  };
+  int r0 = (int)blockIdx.x * 32 + grp;
+  Entry nxt[2] = {entry(r0, 0), entry(r0 + 16, 1)};
+  for (; r0 < R; r0 += stride) {
+    const Entry cur[2] = {nxt[0], nxt[1]};
+    v4u kr[2], vr[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u)
-      if (slot[u] >= 0) {
-        Kd[u][c] = kr[u];
-        Vd[u][c] = vr[u];
+      if (cur[u].slot >= 0) {
+        const v4u *Ks, *Vs;
+        fill_rows_of(src, cur[u].p, Hkv, N, Ks, Vs);
+        kr[u] = Ks[(size_t)cur[u].tok * kRowU4 + c];
+        vr[u] = Vs[(size_t)cur[u].tok * kRowU4 + c];
+      }
+    nxt[0] = entry(r0 + stride, 0);
+    nxt[1] = entry(r0 + stride + 16, 1);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      if (cur[u].slot >= 0) {
+        K_slots[((size_t)cur[u].p * k_max + cur[u].slot) * kRowU4 + c] = kr[u];
+        V_slots[((size_t)cur[u].p * k_max + cur[u].slot) * kRowU4 + c] = vr[u];
       }
   }
 }
