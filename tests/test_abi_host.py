@@ -88,6 +88,7 @@ def test_workspace_size_and_layout(lib):
     (dict(B=2, flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_STAGGER | Q.QSAC_FLAG_FILL_KERNEL), Q.QSAC_EINVAL),
     (dict(B=2, flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_STAGGER | Q.QSAC_FLAG_PUSH_FILL), Q.QSAC_EINVAL),
     (dict(B=2, flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_STAGGER | Q.QSAC_FLAG_PROFILE), Q.QSAC_EINVAL),
+    (dict(B=4097, flags=Q.QSAC_FLAG_DRY_RUN | Q.QSAC_FLAG_STAGGER), Q.QSAC_EINVAL),                   # more than 8192 pairs
 ])
 def test_bad_configs_are_rejected(lib, kw, code):
     a = dict(B=1, Hq=8, Hkv=2, N=4096, k_max=256, dtype=Q.QSAC_F16, flags=Q.QSAC_FLAG_DRY_RUN, importance=None, D=128,
