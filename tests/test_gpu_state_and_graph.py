@@ -114,6 +114,33 @@ def test_staggered_schedule_matches_the_oracle(H, N, k, host, dtype):
     sess.close()
 
 
+def test_staggered_schedule_with_resident_heads_sink_tokens_and_append_buffer(H):
+    """Every optional tensor of the step is sliced with the batch: resident heads (their host rows poisoned, as
+    in the resident-caching test), sink / recent tokens and an append-only buffer that grows by a row per step."""
+    B, Hq, Hkv, N, k, cap = 3, 8, 4, 5000, 300, 12
+    n_sink, n_recent = 4, 16
+    K, V = W.make_kv(B, Hkv, N, 128, "bf16", 95)
+    Ka, Va = W.make_kv(B, Hkv, cap, 128, "bf16", 96)
+    res_slot = [-1, 0, -1, 1]
+    K_bad, V_bad = K.clone(), V.clone()
+    for h in (1, 3):
+        K_bad[:, h] = 7.0
+        V_bad[:, h] = -3.0
+    V_res = torch.stack([V[:, 1], V[:, 3]], dim=1).contiguous().cuda()
+    sess = Q.Session(B, Hq, Hkv, N, k, "bf16", K.cuda(), K_bad.pin_memory(), V_bad.pin_memory(),
+                     flags=Q.QSAC_FLAG_STAGGER, V_res=V_res, res_slot=res_slot, side_stream=True, n_sink=n_sink,
+                     n_recent=n_recent, K_app=Ka.cuda(), V_app=Va.cuda())
+    par = H.Parity(sess, "bf16", W.bits(K), W.bits(K), W.bits(V), n_sink=n_sink, n_recent=n_recent,
+                   Kapp_b=W.bits(Ka), Vapp_b=W.bits(Va))
+    chain = W.QueryChain(B, Hq, 128, 0.95, 95)
+    for t in range(cap):
+        sess.set_appended(t + 1)
+        par.step(chain.next(), 0.9, k, label=f"staggered step {t} with every optional tensor")
+    st = sess.stats()
+    assert par.n_reuse > 0 and 0 < st["resident_rows"] < st["slot_misses"]
+    sess.close()
+
+
 def test_staggered_schedule_replays_from_a_graph(H):
     """The staggered step forks to stream_side and joins again inside one capture; replays equal eager steps."""
     B, Hq, Hkv, N, k, steps = 4, 8, 2, 9000, 256, 16
