@@ -570,6 +570,10 @@ def main():
         st = head["staggered"]
         line["schedules"] = {"plain": {"steps_per_s": r4(head["steps_per_s"]), "ms_per_step": r4(head["ms_per_step"])},
                              "staggered": {k: (v if k == "slices" else r4(v)) for k, v in st.items()}}
+        if "stage_us" in head:
+            # (serial - overlapped) / fill time, the fill time being the fetching attention kernel's on one stream
+            line["schedules"]["staggered"]["overlap_efficiency"] = r4(
+                (head["ms_per_step"] - st["ms_per_step"]) * 1e3 / head["stage_us"]["attn"])
         if st["steps_per_s"] > head["steps_per_s"]:
             # the headline is the faster of the two schedules; the stage times and rooflines below are taken kernel by
             # kernel on one stream (the plain schedule), where each kernel has the machine to itself
