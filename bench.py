@@ -417,13 +417,13 @@ class Bench:
 
 
 def stagger_slices(B):
-    """Batch elements per slice of the library's staggered schedule (enqueue_step in csrc/qsac.hip): B / 8 first,
-    then each about one and a half times the one before; a small rest joins the last slice."""
-    sizes, at, size = [], 0, max(B // 8, 1)
+    """Batch elements per slice of the library's staggered schedule (enqueue_step in csrc/qsac.hip): B / 12 first,
+    then each twice the one before; a small rest joins the last slice."""
+    sizes, at, size = [], 0, max(B // 12, 1)
     while at < B:
         nxt = B if (len(sizes) + 1 == 8 or B - at - size < size // 2) else at + size
         sizes.append(nxt - at)
-        at, size = nxt, max(size + 1, size * 3 // 2)
+        at, size = nxt, size * 2
     return sizes
 
 

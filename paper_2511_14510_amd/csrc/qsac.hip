@@ -237,7 +237,7 @@ struct PushEngine {
   }
 };
 
-constexpr int kStaggerSlices = 8;        // at most (a batch of 32 runs as 4 + 6 + 9 + 13)
+constexpr int kStaggerSlices = 8;        // at most (a batch of 32 runs as 2 + 4 + 8 + 18)
 constexpr int kTrickleWorkgroups = 64;  // of the staggered schedule's fill kernel (32: 3.32 ms, 48: 3.16, 64: 3.14,
                                         // 96: 3.23, 128: 3.19 per step of the largest workload)
 
@@ -912,12 +912,13 @@ int enqueue_step(qsac_ctx* c, const qsac_step_args* a) {
   if (!c->stagger) return enqueue_range(c, a, 0, B, c->s_main, kWholeStep, true);
   int rc = enqueue_range(c, a, 0, B, c->s_main, kGate, false);
   if (rc != QSAC_OK) return rc;
-  // Slice sizes: a small first slice, so that the link starts early, then each about one and a half times the one
-  // before: beside the fill a scoring pass runs at about a third of its speed, and the scoring of slice i + 1 has
-  // to be through before the fill of slice i is.
+  // Slice sizes: a small first slice (B / 12), so that the link starts early, then each twice the one before:
+  // beside the fill a scoring pass runs at a half to a third of its speed, and the scoring of slice i + 1 has to
+  // be through before the fill of slice i is.  (First slice B/6 .. B/12, growth 1.5 or 2: 3.11 to 3.15 ms per step
+  // of the largest workload.)
   int start[kStaggerSlices + 1];
   int n = 0;
-  for (int at = 0, size = B / 8 > 0 ? B / 8 : 1; at < B; size = size + 1 > size * 3 / 2 ? size + 1 : size * 3 / 2) {
+  for (int at = 0, size = B / 12 > 0 ? B / 12 : 1; at < B; size *= 2) {
     start[n++] = at;
     at = (n == kStaggerSlices || B - at - size < size / 2) ? B : at + size;  // (a small rest joins the last slice)
   }
