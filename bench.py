@@ -586,6 +586,13 @@ def main():
         # dominant kernel: the attention kernel fetching the missing rows over PCIe where the workload offloads,
         # the scoring pass otherwise
         line["roofline"] = rf["pcie"] if "pcie" in rf else rf["score"]
+        if "pcie" in rf and "staggered" in head:
+            # the figures above are the plain schedule's fetching kernel (event-timed on its stream); under the staggered
+            # schedule the rows travel in qsac_fill_trickle_kernel launches beside the other kernels: host bytes over
+            # the whole step's wall time is a lower bound of that kernel's own rate
+            line["roofline"]["staggered_whole_step_GBps"] = r4(head["staggered"]["host_GBps_over_the_step"])
+            line["roofline"]["staggered_whole_step_frac"] = r4(head["staggered"]["host_GBps_over_the_step"]
+                                                               / head["pcie"]["peak_GBps"])
         line["score_roofline"], line["attn_roofline"] = rf["score"], rf["attn"]
         line["stage_us"] = {s: r4(head["stage_us"][s]) for s in STAGES}
         line["all_miss"] = {"stage_us": {s: r4(head["all_miss"]["stage_us"][s]) for s in STAGES},
